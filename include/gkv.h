@@ -1,0 +1,184 @@
+/*
+ * gkv.h - C ABI of the G-KV decode/evict hot path for AMD MI355X (gfx950).
+ *
+ * Per layer and decode step the path is: attention of the newest query over a
+ * budget-capped KV cache; every s steps, the local score of each cached token
+ * from the observation window (paper: Preliminary, Eq. 1 and Eq. 2), the
+ * global score that merges it with the token's decayed history (paper:
+ * Section 4, the max / average / summation forms), top-(b-w) selection per
+ * KV head and compaction of K, V and the recorded scores.
+ *
+ * Notation (paper, Preliminary): h_q query heads, h_kv KV heads, g = h_q/h_kv,
+ * d head dim, l cache length, b budget, w observation window, s compression
+ * interval, alpha memory-decay rate.  Query head i reads KV head i / g.
+ * A "unit" is one (layer, sequence, KV head).  L = n_layers, B = batch.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates or frees device memory.  `workspace` is device memory of
+ *     at least gkv_workspace_bytes() bytes, zeroed once with
+ *     gkv_workspace_init() and then left to the library.
+ *   - `stream` is a hipStream_t passed as void*; calls only enqueue work on it
+ *     and return.  No host synchronisation, no device-to-host copies.  Lengths
+ *     live on the device (d_len, d_n_hist); `len_max_host` is only an upper
+ *     bound the host knows, used to size launches and to reject overflow.
+ *   - Arrays are row-major with the last index contiguous, base pointers 16-byte
+ *     aligned.  Element type of q, k_new, v_new, K, V, qwin, out is
+ *     config.dtype; scores are float; lengths, positions, indices are int32.
+ *   - K cache layout: each KV head's [capacity, d] block is stored in tiles of
+ *     16 rows; inside a tile the 16-byte chunks are chunk-major, i.e. element
+ *     (row n, channel c) sits at element offset
+ *         (n/16)*16*d + (c/E)*16*E + (n%16)*E + c%E,   E = 16/sizeof(element),
+ *     which gkv_k_offset() returns.  This makes a wavefront's matrix-core
+ *     operand load of a 16-key tile one contiguous 1 KiB read.  V is plain
+ *     row-major [capacity, d].
+ *   - Return value: GKV_OK or an error code; arguments are validated on the
+ *     host before anything is enqueued, a failed call enqueues nothing.
+ *     Results are deterministic: same inputs, same bits.
+ *   - A compression call is a no-op for every (layer, sequence) whose length is
+ *     not above the budget, so ragged batches are legal.
+ */
+#ifndef GKV_H
+#define GKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GKV_OK = 0,
+  GKV_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, alpha outside [0,1], w > s, w >= b ... */
+  GKV_ERR_SHAPE = 2,         /* shape the kernels do not support (see gkv_create) */
+  GKV_ERR_WORKSPACE = 3,     /* workspace pointer missing */
+  GKV_ERR_HIP = 4,           /* a HIP runtime call failed */
+  GKV_ERR_UNSUPPORTED = 5,
+  GKV_ERR_OVERFLOW = 6       /* len_max_host would exceed the capacity */
+} gkv_status;
+
+typedef enum { GKV_F32 = 0, GKV_BF16 = 1 } gkv_dtype;
+
+/* Section 4: the three forms of the global score. */
+typedef enum { GKV_COMBINE_MAX = 0, GKV_COMBINE_AVG = 1, GKV_COMBINE_SUM = 2 } gkv_combine;
+
+typedef struct gkv_config {
+  int32_t n_layers, batch;          /* L, B */
+  int32_t n_q_heads, n_kv_heads;    /* h_q, h_kv; h_q % h_kv == 0 */
+  int32_t head_dim;                 /* d; multiple of 16/sizeof(element) */
+  int32_t budget, window, interval; /* b, w, s;  w <= s, w < b */
+  int32_t capacity;                 /* rows per KV head; >= b + s, multiple of 32 */
+  int32_t dtype;                    /* gkv_dtype */
+  int32_t combine;                  /* gkv_combine */
+  float alpha;                      /* memory-decay rate in [0,1]; 0 = local score only */
+  float softmax_scale;              /* 0 means 1/sqrt(d) as in Eq. 1 */
+} gkv_config;
+
+typedef struct gkv_ctx gkv_ctx;     /* opaque, host memory only */
+
+/* Validates the configuration and builds a host-side context.  Touches no GPU. */
+gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx);
+void gkv_destroy(gkv_ctx* ctx);
+const char* gkv_status_string(gkv_status st);
+
+/* Bytes of device workspace the calls below need for this context. */
+gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes);
+/* Enqueues a fill kernel that zeroes the workspace's counters.  Call once. */
+gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream);
+
+/* Host-only helpers.
+ * gkv_cache_bytes: bytes of K+V cache and of the score cache F for the whole
+ * configuration at `rows` rows per KV head (paper, appendix "Memory Analysis":
+ * rows = b + s for the KV cache between compressions, b - w scores per head).
+ * gkv_k_offset: element offset of (row, channel) inside one KV head's K block. */
+gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_elem_bytes,
+                           size_t* kv_bytes, size_t* score_bytes);
+int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel);
+
+/* Tuning knobs (host only): "attend_splits" (0 = automatic), "force_generic"
+ * (1 = use the plain vector-ALU kernels even where matrix-core kernels exist). */
+gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
+
+/*
+ * Every decode step (paper, Preliminary: the cache the newest token attends to;
+ * evicted entries are invisible to later tokens).  For every (layer, sequence)
+ * with length len = d_len[l,b]:
+ *   appends k_new, v_new as row len of K, V and pos[len] = step (skipped when
+ *   k_new is NULL or len == capacity), stores q in slot step % w of the window
+ *   ring qwin, attends q over rows [0, len] including the new one:
+ *   out[i] = softmax(q[i] . K[i/g]^T * scale) V[i/g], and sets d_len = len + 1.
+ * q, out [L,B,h_q,d]; k_new, v_new [L,B,h_kv,d]; K, V [L,B,h_kv,capacity,d];
+ * pos [L,B,h_kv,capacity]; qwin [L,B,h_q,w,d]; d_len [L,B].
+ * len_max_host: host bound with every len <= len_max_host < capacity.
+ */
+gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                             void* K, void* V, int32_t* pos, int32_t step, void* qwin,
+                             int32_t* d_len, int32_t len_max_host, void* out,
+                             void* workspace, void* stream);
+
+/*
+ * Local score (paper, Preliminary, Eq. 1 then group max-reduce then Eq. 2).
+ * With l = d_len, c = l - w: window row k is the query decoded at step
+ * step - w + 1 + k (ring slot of that step), normalised over rows [0, c + k]
+ * (the keys it saw when decoded); S[n] = (1/w) sum_k max_{heads of the group}
+ * A[head, k, n] for the candidates n < c.  Entries n >= c are not written.
+ * `step` is the step index of the latest gkv_attend_decode.  S [L,B,h_kv,capacity].
+ */
+gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_len,
+                            int32_t step, int32_t len_max_host, float* S,
+                            void* workspace, void* stream);
+
+/*
+ * Global score (paper, Section 4).  Sn = S / max_{n<c} S per KV head;
+ * F_out[n] = combine(alpha * F_hist[n], Sn[n]) for n < d_n_hist, else Sn[n].
+ * combine is max, alpha*F + (1-alpha)*Sn, or alpha*F + Sn.  A zero maximum
+ * gives Sn = 0.  S, F_hist, F_out [L,B,h_kv,capacity]; d_n_hist [L,B].
+ */
+gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
+                             const int32_t* d_n_hist, const int32_t* d_len, int32_t len_max_host,
+                             float* F_out, void* stream);
+
+/*
+ * Top-(b-w) selection per unit (paper, Preliminary and Section 4): ascending
+ * indices of the b-w largest F among candidates [0, l-w); equal scores: lower
+ * index first.  keep_idx [L,B,h_kv,b-w].  Always writes valid in-range indices,
+ * whatever the score bits.
+ */
+gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_len,
+                           int32_t len_max_host, int32_t* keep_idx, void* workspace, void* stream);
+
+/*
+ * Compaction (paper, Section 4: the kept entries' scores are recorded for the
+ * next compression; appendix "Memory Analysis": cache of b rows, b-w scores).
+ * In place and stable: row keep_idx[r] moves to r for r < b-w (K, V, pos),
+ * F_hist[r] = F[keep_idx[r]], the w window rows [l-w, l) move to [b-w, b);
+ * then d_len = b, d_n_hist = b-w.
+ */
+gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
+                       float* F_hist, int32_t* pos, int32_t* d_len, int32_t* d_n_hist,
+                       void* workspace, void* stream);
+
+/* The four compression calls above in order, on caller-provided S, F, keep_idx. */
+gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
+                     int32_t* d_len, int32_t* d_n_hist, int32_t step, int32_t len_max_host,
+                     float* S, float* F, int32_t* keep_idx, void* workspace, void* stream);
+
+/*
+ * Kernel timing for benchmarks.  While enabled, each kernel launch is bracketed
+ * by HIP events on the launch stream that record the kernel's own begin and
+ * end; gkv_profile_read synchronises those events and returns the total
+ * milliseconds and launch count of one kernel class since the last reset.
+ */
+typedef enum {
+  GKV_K_ATTEND = 0, GKV_K_SCORE = 1, GKV_K_GLOBAL = 2, GKV_K_TOPK = 3, GKV_K_COMPACT = 4,
+  GKV_K_COUNT = 5
+} gkv_kernel_id;
+gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on);
+gkv_status gkv_profile_read(gkv_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches);
+gkv_status gkv_profile_reset(gkv_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GKV_H */

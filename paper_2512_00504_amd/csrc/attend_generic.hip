@@ -1,0 +1,109 @@
+// Decode attention, plain vector-ALU version for any dtype / head shape.
+// One workgroup per unit (layer, sequence, KV head); fp32 arithmetic throughout.
+// Used for the fp32 configuration and for shapes the matrix-core kernel does not cover.
+#include "gkv_internal.h"
+
+namespace {
+
+// Dynamic LDS: float prob[cap + 1]; float qs[d]; float red[8]; int misc[2]
+template <typename T>
+__global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendArgs a) {
+  extern __shared__ float smem[];
+  constexpr int EPC = Elem<T>::EPC;
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x;
+  const int j = unit % dm.Hkv;
+  const int lb = unit / dm.Hkv;
+  const int d = dm.d, cap = dm.cap, g = dm.g;
+  float* prob = smem;
+  float* qs = prob + cap + 1;
+  float* red = qs + d;
+  int* misc = (int*)(red + 8);
+
+  if (tid == 0) misc[0] = a.d_len[lb];
+  __syncthreads();
+  const int len0 = misc[0];
+  if (tid == 0) {
+    // Every workgroup of this (layer, sequence) has read the length once it has taken a
+    // ticket; the last one to arrive publishes the new length and re-arms the counter.
+    const bool grows = (a.k_new != nullptr) && (len0 < cap);
+    int old = atomicAdd(&a.ws.len_ticket[lb], 1);
+    if (old == dm.Hkv - 1) {
+      a.ws.len_ticket[lb] = 0;
+      if (grows) a.d_len[lb] = len0 + 1;
+    }
+  }
+  const bool has_new = (a.k_new != nullptr) && (len0 < cap);
+  const int n_tot = len0 + (has_new ? 1 : 0);
+
+  const T* Kh = (const T*)a.K + (size_t)unit * cap * d;
+  const T* Vh = (const T*)a.V + (size_t)unit * cap * d;
+  const T* kn = has_new ? (const T*)a.k_new + (size_t)unit * d : nullptr;
+  const T* vn = has_new ? (const T*)a.v_new + (size_t)unit * d : nullptr;
+
+  for (int hi = 0; hi < g; ++hi) {
+    const int head = j * g + hi;
+    const T* qh = (const T*)a.q + ((size_t)lb * dm.Hq + head) * d;
+    __syncthreads();
+    for (int c = tid; c < d; c += blockDim.x) qs[c] = Elem<T>::ld(qh + c);
+    __syncthreads();
+    // logits
+    float mx = -INFINITY;
+    for (int n = tid; n < n_tot; n += blockDim.x) {
+      float acc = 0.f;
+      if (n == len0 && has_new) {
+        for (int c = 0; c < d; ++c) acc = fmaf(qs[c], Elem<T>::ld(kn + c), acc);
+      } else {
+        for (int c = 0; c < d; ++c) acc = fmaf(qs[c], Elem<T>::ld(Kh + k_tiled_offset<EPC>(n, c, d)), acc);
+      }
+      acc *= dm.scale;
+      prob[n] = acc;
+      mx = fmaxf(mx, acc);
+    }
+    mx = block_max(mx, red);
+    float sm = 0.f;
+    for (int n = tid; n < n_tot; n += blockDim.x) {
+      float e = expf(prob[n] - mx);
+      prob[n] = e;
+      sm += e;
+    }
+    sm = block_sum(sm, red);          // also makes prob[] visible to all threads
+    const float inv = 1.f / sm;
+    T* oh = (T*)a.out + ((size_t)lb * dm.Hq + head) * d;
+    for (int c = tid; c < d; c += blockDim.x) {
+      float acc = 0.f;
+      for (int n = 0; n < len0; ++n) acc = fmaf(prob[n], Elem<T>::ld(Vh + (size_t)n * d + c), acc);
+      if (has_new) acc = fmaf(prob[len0], Elem<T>::ld(vn + c), acc);
+      Elem<T>::st(oh + c, acc * inv);
+    }
+  }
+
+  // Append the new row and push q into the window ring, after all reads of this unit's cache.
+  __syncthreads();
+  if (has_new) {
+    T* Kw = (T*)a.K + (size_t)unit * cap * d;
+    T* Vw = (T*)a.V + (size_t)unit * cap * d;
+    for (int c = tid; c < d; c += blockDim.x) {
+      Kw[k_tiled_offset<EPC>(len0, c, d)] = kn[c];
+      Vw[(size_t)len0 * d + c] = vn[c];
+    }
+    if (tid == 0) a.pos[(size_t)unit * cap + len0] = a.step;
+  }
+  const int slot = a.step % dm.w;
+  for (int x = tid; x < g * d; x += blockDim.x) {
+    const int hi = x / d, c = x % d;
+    const int head = j * g + hi;
+    ((T*)a.qwin)[(((size_t)lb * dm.Hq + head) * dm.w + slot) * d + c] =
+        ((const T*)a.q)[((size_t)lb * dm.Hq + head) * d + c];
+  }
+}
+
+}  // namespace
+
+hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  const size_t shmem = sizeof(float) * (dm.cap + 1 + dm.d + 8) + 2 * sizeof(int);
+  if (dtype == GKV_F32)
+    return gkv_launch(ln, attend_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);
+  return gkv_launch(ln, attend_generic_kernel<uint16_t>, dim3(units), dim3(256), shmem, dm, a);
+}

@@ -1,0 +1,246 @@
+// Global-score update, top-(b-w) selection and in-place compaction.  One workgroup of 256
+// threads per unit; all score arithmetic in fp32, all index work in integers.
+#include "gkv_internal.h"
+
+namespace {
+
+// ---- helpers -------------------------------------------------------------------------------
+// Inclusive scan over the 256 threads of a block; `tmp` holds 4 ints of LDS.
+__device__ __forceinline__ int block_inclusive_scan(int v, int* tmp) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  __syncthreads();
+  if (lane == 63) tmp[wv] = v;
+  __syncthreads();
+  int add = 0;
+  for (int i = 0; i < wv; ++i) add += tmp[i];
+  return v + add;
+}
+
+// Monotone map float -> uint32 (larger float, larger key); -0 is folded onto +0 first.
+__device__ __forceinline__ uint32_t sortable_key(float f) {
+  f = f + 0.0f;
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---- global score (Section 4) --------------------------------------------------------------
+__global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const float* __restrict__ S,
+                                                            const float* __restrict__ F_hist,
+                                                            const int32_t* __restrict__ d_n_hist,
+                                                            const int32_t* __restrict__ d_len,
+                                                            float* __restrict__ F_out) {
+  __shared__ float red[8];
+  const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
+  const int l = d_len[lb];
+  if (l <= dm.b || l > dm.cap) return;
+  const int c = l - dm.w;
+  int n_hist = d_n_hist[lb];
+  n_hist = n_hist < 0 ? 0 : (n_hist > c ? c : n_hist);
+  const float* Su = S + (size_t)unit * dm.cap;
+  const float* Hu = F_hist + (size_t)unit * dm.cap;
+  float* Fu = F_out + (size_t)unit * dm.cap;
+  float mx = 0.f;
+  for (int n = tid; n < c; n += 256) mx = fmaxf(mx, Su[n]);
+  mx = block_max(mx, red);
+  for (int n = tid; n < c; n += 256) {
+    const float sn = mx > 0.f ? Su[n] / mx : 0.f;
+    float f = sn;
+    if (n < n_hist) {
+      const float h = dm.alpha * Hu[n];
+      f = dm.combine == GKV_COMBINE_MAX ? fmaxf(h, sn)
+        : dm.combine == GKV_COMBINE_AVG ? h + (1.f - dm.alpha) * sn
+                                        : h + sn;
+    }
+    Fu[n] = f;
+  }
+}
+
+// ---- top-(b-w): exact radix select on the float bits, ties to the lower index ---------------
+// Dynamic LDS: uint32 keys[cap]
+__global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const float* __restrict__ F,
+                                                          const int32_t* __restrict__ d_len,
+                                                          int32_t* __restrict__ keep_idx) {
+  extern __shared__ uint32_t keys[];
+  __shared__ int hist[256];
+  __shared__ int tmp[4];
+  __shared__ int sel[2];
+  const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
+  const int l = d_len[lb];
+  if (l <= dm.b || l > dm.cap) return;
+  const int c = l - dm.w;
+  const int k = dm.b - dm.w;                   // c > k because l > b
+  const float* Fu = F + (size_t)unit * dm.cap;
+  for (int n = tid; n < c; n += 256) keys[n] = sortable_key(Fu[n]);
+
+  uint32_t prefix = 0, mask = 0;
+  int krem = k;
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = 8 * pass;
+    hist[tid] = 0;
+    __syncthreads();                            // also orders keys[] writes before the first pass
+    for (int n = tid; n < c; n += 256) {
+      const uint32_t key = keys[n];
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    const int v = hist[255 - tid];              // thread t looks at bin 255-t: descending bins
+    const int incl = block_inclusive_scan(v, tmp);   // entries in bins >= 255-t
+    if (incl >= krem && incl - v < krem) { sel[0] = 255 - tid; sel[1] = krem - (incl - v); }
+    __syncthreads();
+    prefix |= ((uint32_t)sel[0]) << shift;
+    mask |= 255u << shift;
+    krem = sel[1];
+    __syncthreads();
+  }
+  // prefix is now the k-th largest key; keep everything above it and the first `krem` equal to it.
+  const int per = (c + 255) / 256;
+  const int lo = tid * per, hi = min(c, lo + per);
+  int n_eq = 0;
+  for (int n = lo; n < hi; ++n) n_eq += (keys[n] == prefix);
+  int eq_before = block_inclusive_scan(n_eq, tmp) - n_eq;
+  int n_keep = 0;
+  {
+    int eq = eq_before;
+    for (int n = lo; n < hi; ++n) {
+      const uint32_t key = keys[n];
+      if (key > prefix) ++n_keep;
+      else if (key == prefix) { n_keep += (eq < krem); ++eq; }
+    }
+  }
+  int out = block_inclusive_scan(n_keep, tmp) - n_keep;
+  int32_t* Ku = keep_idx + (size_t)unit * k;
+  int eq = eq_before;
+  for (int n = lo; n < hi; ++n) {
+    const uint32_t key = keys[n];
+    bool keep = key > prefix;
+    if (key == prefix) { keep = eq < krem; ++eq; }
+    if (keep && out < k) Ku[out++] = n;
+  }
+}
+
+// ---- compaction ----------------------------------------------------------------------------
+// grid (units, 2): y = 0 moves K (tiled layout), pos and F_hist; y = 1 moves V (row-major).
+// Rows are produced in ascending chunks: load every source piece of the chunk, barrier, store.
+// Destination index <= source index and sources ascend, so a chunk's stores never touch a
+// source that a later chunk still has to read.
+template <int PPT>
+__global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const int32_t* __restrict__ keep_idx,
+                                                      const float* __restrict__ F, void* K, void* V,
+                                                      float* __restrict__ F_hist, int32_t* pos,
+                                                      const int32_t* __restrict__ d_len) {
+  __shared__ int red_i[4];
+  const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
+  const bool isK = blockIdx.y == 0;
+  const int l = d_len[lb];
+  if (l <= dm.b || l > dm.cap) return;
+  const int c = l - dm.w, k = dm.b - dm.w, b = dm.b;
+  const int32_t* Ku = keep_idx + (size_t)unit * k;
+
+  // first destination row whose source differs from it
+  int first = k;
+  for (int n = tid; n < k; n += 256)
+    if (Ku[n] != n) { first = n; break; }        // ascending per thread: the first hit is its minimum
+  for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o));
+  if ((tid & 63) == 0) red_i[tid >> 6] = first;
+  __syncthreads();
+  first = min(min(red_i[0], red_i[1]), min(red_i[2], red_i[3]));
+
+  if (isK) {
+    float* Hu = F_hist + (size_t)unit * dm.cap;
+    const float* Fu = F + (size_t)unit * dm.cap;
+    for (int n = tid; n < k; n += 256) {
+      int src = Ku[n];
+      src = src < 0 ? 0 : (src >= c ? c - 1 : src);
+      Hu[n] = Fu[src];
+    }
+  }
+
+  const int NP = dm.d * esz / 16;                // 16-byte pieces per row
+  const int R = (256 * PPT) / NP;                // rows per chunk
+  uint4* base = (uint4*)((char*)(isK ? K : V) + (size_t)unit * dm.cap * dm.d * esz);
+  int32_t* pu = pos + (size_t)unit * dm.cap;
+
+  for (int r0 = first; r0 < b; r0 += R) {
+    uint4 buf[PPT];
+    int dst[PPT];
+    int pos_val = 0;
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+      const int x = tid + 256 * i;
+      const int rr = x / NP, piece = x % NP;
+      const int row = r0 + rr;
+      dst[i] = -1;
+      if (rr < R && row < b) {
+        int src = row < k ? Ku[row] : c + (row - k);
+        src = src < 0 ? 0 : (src >= l ? l - 1 : src);
+        const int so = isK ? ((src >> 4) * 16 * NP + piece * 16 + (src & 15)) : (src * NP + piece);
+        dst[i] = isK ? ((row >> 4) * 16 * NP + piece * 16 + (row & 15)) : (row * NP + piece);
+        buf[i] = base[so];
+      }
+    }
+    const int prow = r0 + tid;
+    const bool do_pos = isK && tid < R && prow < b;
+    if (do_pos) {
+      int src = prow < k ? Ku[prow] : c + (prow - k);
+      src = src < 0 ? 0 : (src >= l ? l - 1 : src);
+      pos_val = pu[src];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PPT; ++i)
+      if (dst[i] >= 0) base[dst[i]] = buf[i];
+    if (do_pos) pu[prow] = pos_val;
+  }
+}
+
+__global__ void finalize_lengths_kernel(GkvDims dm, int32_t* d_len, int32_t* d_n_hist) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= dm.L * dm.B) return;
+  const int l = d_len[i];
+  if (l > dm.b && l <= dm.cap) {
+    d_len[i] = dm.b;
+    d_n_hist[i] = dm.b - dm.w;
+  }
+}
+
+__global__ void fill_zero_kernel(int32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+}  // namespace
+
+hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
+                                    const float* F_hist, const int32_t* d_n_hist,
+                                    const int32_t* d_len, float* F_out) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, global_update_kernel, dim3(units), dim3(256), 0, dm, S, F_hist, d_n_hist, d_len, F_out);
+}
+
+hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
+                                  const int32_t* d_len, int32_t* keep_idx) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, select_topk_kernel, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, F, d_len, keep_idx);
+}
+
+hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
+                              const float* F, void* K, void* V, float* F_hist, int32_t* pos,
+                              int32_t* d_len, int32_t* d_n_hist) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  hipError_t e = gkv_launch(ln, compact_kernel<4>, dim3(units, 2), dim3(256), 0, dm, esz, keep_idx, F, K, V,
+                            F_hist, pos, (const int32_t*)d_len);
+  if (e != hipSuccess) return e;
+  const int nlb = dm.L * dm.B;
+  GkvLaunch plain{ln.ctx, -1, ln.stream};
+  return gkv_launch(plain, finalize_lengths_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_len, d_n_hist);
+}
+
+hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n) {
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}

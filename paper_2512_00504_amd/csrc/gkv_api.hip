@@ -1,0 +1,309 @@
+// C-ABI layer: argument validation, workspace carving, kernel selection, profiling events.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "gkv_internal.h"
+
+bool gkv_score_mfma_supported(int g, int w);
+
+// ---- profiling ----------------------------------------------------------------------------------
+struct GkvProfile {
+  bool on = false;
+  struct Rec { hipEvent_t e0, e1; };
+  std::vector<Rec> recs[GKV_K_COUNT];
+  double done_ms[GKV_K_COUNT] = {0, 0, 0, 0, 0};
+  int64_t done_n[GKV_K_COUNT] = {0, 0, 0, 0, 0};
+};
+
+void gkv_profile_events(const GkvLaunch& ln, hipEvent_t* start, hipEvent_t* stop) {
+  *start = nullptr; *stop = nullptr;
+  GkvProfile* p = ln.ctx ? ln.ctx->prof : nullptr;
+  if (!p || !p->on || ln.kernel_id < 0 || ln.kernel_id >= GKV_K_COUNT) return;
+  GkvProfile::Rec rec;
+  if (hipEventCreate(&rec.e0) != hipSuccess) return;
+  if (hipEventCreate(&rec.e1) != hipSuccess) { (void)hipEventDestroy(rec.e0); return; }
+  p->recs[ln.kernel_id].push_back(rec);
+  *start = rec.e0; *stop = rec.e1;
+}
+
+static void profile_drain(GkvProfile* p, int k) {
+  for (auto& rec : p->recs[k]) {
+    float ms = 0.f;
+    if (hipEventSynchronize(rec.e1) == hipSuccess && hipEventElapsedTime(&ms, rec.e0, rec.e1) == hipSuccess) {
+      p->done_ms[k] += ms;
+      p->done_n[k] += 1;
+    }
+    (void)hipEventDestroy(rec.e0);
+    (void)hipEventDestroy(rec.e1);
+  }
+  p->recs[k].clear();
+}
+
+// ---- context ------------------------------------------------------------------------------------
+static gkv_status validate_config(const gkv_config* c) {
+  if (!c) return GKV_ERR_INVALID_ARG;
+  if (c->dtype != GKV_F32 && c->dtype != GKV_BF16) return GKV_ERR_INVALID_ARG;
+  if (c->combine < GKV_COMBINE_MAX || c->combine > GKV_COMBINE_SUM) return GKV_ERR_INVALID_ARG;
+  if (c->n_layers < 1 || c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1)
+    return GKV_ERR_INVALID_ARG;
+  if (c->n_q_heads % c->n_kv_heads != 0) return GKV_ERR_INVALID_ARG;
+  if (c->budget < 2 || c->window < 1 || c->interval < 1) return GKV_ERR_INVALID_ARG;
+  if (c->window > c->interval || c->window >= c->budget) return GKV_ERR_INVALID_ARG;
+  if (!(c->alpha >= 0.f && c->alpha <= 1.f)) return GKV_ERR_INVALID_ARG;
+  if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return GKV_ERR_INVALID_ARG;
+  const int esz = c->dtype == GKV_F32 ? 4 : 2;
+  const int epc = 16 / esz;
+  if (c->head_dim % epc != 0 || c->head_dim > 1024) return GKV_ERR_SHAPE;
+  if (c->capacity < c->budget + c->interval || c->capacity % 32 != 0 || c->capacity > 16384)
+    return GKV_ERR_SHAPE;
+  const int64_t units = (int64_t)c->n_layers * c->batch * c->n_kv_heads;
+  if (units > (1 << 24)) return GKV_ERR_SHAPE;
+  return GKV_OK;
+}
+
+extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
+  if (!out_ctx) return GKV_ERR_INVALID_ARG;
+  *out_ctx = nullptr;
+  gkv_status st = validate_config(cfg);
+  if (st != GKV_OK) return st;
+  gkv_ctx* c = new (std::nothrow) gkv_ctx();
+  if (!c) return GKV_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  GkvDims& d = c->dims;
+  d.L = cfg->n_layers; d.B = cfg->batch; d.Hq = cfg->n_q_heads; d.Hkv = cfg->n_kv_heads;
+  d.d = cfg->head_dim; d.g = cfg->n_q_heads / cfg->n_kv_heads;
+  d.b = cfg->budget; d.w = cfg->window; d.s = cfg->interval; d.cap = cfg->capacity;
+  d.combine = cfg->combine; d.alpha = cfg->alpha;
+  d.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : (float)(1.0 / sqrt((double)cfg->head_dim));
+  c->esz = cfg->dtype == GKV_F32 ? 4 : 2;
+  c->attend_splits = 0;
+  c->force_generic = 0;
+  c->mfma_ok = cfg->dtype == GKV_BF16 && d.d == 128 && d.g <= 16;
+  c->prof = new (std::nothrow) GkvProfile();
+  *out_ctx = c;
+  return GKV_OK;
+}
+
+extern "C" void gkv_destroy(gkv_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->prof) {
+    for (int k = 0; k < GKV_K_COUNT; ++k) profile_drain(ctx->prof, k);
+    delete ctx->prof;
+  }
+  delete ctx;
+}
+
+extern "C" const char* gkv_status_string(gkv_status st) {
+  switch (st) {
+    case GKV_OK: return "ok";
+    case GKV_ERR_INVALID_ARG: return "invalid argument";
+    case GKV_ERR_SHAPE: return "unsupported shape";
+    case GKV_ERR_WORKSPACE: return "workspace missing";
+    case GKV_ERR_HIP: return "HIP runtime error";
+    case GKV_ERR_UNSUPPORTED: return "unsupported";
+    case GKV_ERR_OVERFLOW: return "cache capacity exceeded";
+  }
+  return "unknown status";
+}
+
+static int max_splits(const gkv_ctx* ctx) {
+  // a split workgroup of 4 wavefronts covers 128 keys per round
+  int m = ctx->dims.cap / 128;
+  return m < 1 ? 1 : (m > 64 ? 64 : m);
+}
+
+int gkv_effective_splits(const gkv_ctx* ctx) {
+  const bool mfma = ctx->mfma_ok && !ctx->force_generic;
+  if (!mfma) return 1;
+  const int64_t units = (int64_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
+  int s = ctx->attend_splits;
+  if (s <= 0) s = units >= 512 ? 1 : (int)((1024 + units - 1) / units);
+  const int m = max_splits(ctx);
+  return s > m ? m : s;
+}
+
+static size_t ws_partials_bytes(const gkv_ctx* ctx) {
+  // sized for the largest split count so that "attend_splits" can change without reallocation
+  const bool mfma = ctx->mfma_ok;
+  if (!mfma) return 0;
+  const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
+  int s = ctx->attend_splits > 0 ? ctx->attend_splits : gkv_effective_splits(ctx);
+  if (s > max_splits(ctx)) s = max_splits(ctx);
+  return s > 1 ? units * s * ctx->dims.g * (ctx->dims.d + 2) * sizeof(float) : 0;
+}
+
+GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
+  GkvWorkspace w;
+  char* p = (char*)base;
+  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
+  const size_t units = nlb * ctx->dims.Hkv;
+  w.len_ticket = (int32_t*)p; p += gkv_align256(nlb * 4);
+  w.split_ticket = (int32_t*)p; p += gkv_align256(units * 4);
+  w.partials = (float*)p;
+  return w;
+}
+
+extern "C" gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes) {
+  if (!ctx || !out_bytes) return GKV_ERR_INVALID_ARG;
+  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
+  const size_t units = nlb * ctx->dims.Hkv;
+  *out_bytes = gkv_align256(nlb * 4) + gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx)) + 256;
+  return GKV_OK;
+}
+
+extern "C" gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream) {
+  if (!ctx) return GKV_ERR_INVALID_ARG;
+  if (!workspace) return GKV_ERR_WORKSPACE;
+  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
+  const size_t units = nlb * ctx->dims.Hkv;
+  const size_t n = (gkv_align256(nlb * 4) + gkv_align256(units * 4)) / 4;
+  return gkv_launch_fill_zero((hipStream_t)stream, (int32_t*)workspace, n) == hipSuccess ? GKV_OK : GKV_ERR_HIP;
+}
+
+extern "C" gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_elem_bytes,
+                                      size_t* kv_bytes, size_t* score_bytes) {
+  if (!cfg || rows < 0 || score_elem_bytes < 1) return GKV_ERR_INVALID_ARG;
+  if (cfg->dtype != GKV_F32 && cfg->dtype != GKV_BF16) return GKV_ERR_INVALID_ARG;
+  const size_t esz = cfg->dtype == GKV_F32 ? 4 : 2;
+  const size_t heads = (size_t)cfg->n_layers * cfg->batch * cfg->n_kv_heads;
+  if (kv_bytes) *kv_bytes = heads * (size_t)rows * cfg->head_dim * esz * 2;            // K and V
+  if (score_bytes) {
+    const int64_t n = (int64_t)cfg->budget - cfg->window;
+    *score_bytes = heads * (size_t)(n > 0 ? n : 0) * (size_t)score_elem_bytes;
+  }
+  return GKV_OK;
+}
+
+extern "C" int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel) {
+  if (!cfg || row < 0 || channel < 0 || channel >= cfg->head_dim) return -1;
+  const int epc = cfg->dtype == GKV_F32 ? 4 : 8;
+  const int64_t d = cfg->head_dim;
+  return (int64_t)(row / 16) * 16 * d + (int64_t)(channel / epc) * (16 * epc) + (row % 16) * epc + channel % epc;
+}
+
+extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value) {
+  if (!ctx || !name) return GKV_ERR_INVALID_ARG;
+  if (!strcmp(name, "attend_splits")) {
+    if (value < 0 || value > 64) return GKV_ERR_INVALID_ARG;
+    ctx->attend_splits = value;
+    return GKV_OK;
+  }
+  if (!strcmp(name, "force_generic")) { ctx->force_generic = value != 0; return GKV_OK; }
+  return GKV_ERR_INVALID_ARG;
+}
+
+// ---- the five calls -----------------------------------------------------------------------------
+static bool use_mfma_attend(const gkv_ctx* ctx) { return ctx->mfma_ok && !ctx->force_generic; }
+static bool use_mfma_score(const gkv_ctx* ctx) {
+  return ctx->mfma_ok && !ctx->force_generic && gkv_score_mfma_supported(ctx->dims.g, ctx->dims.w);
+}
+static gkv_status check_len(const gkv_ctx* ctx, int32_t len_max_host, bool appending) {
+  if (len_max_host < 0) return GKV_ERR_INVALID_ARG;
+  if (len_max_host > ctx->dims.cap || (appending && len_max_host >= ctx->dims.cap)) return GKV_ERR_OVERFLOW;
+  return GKV_OK;
+}
+static inline gkv_status hip_status(hipError_t e) { return e == hipSuccess ? GKV_OK : GKV_ERR_HIP; }
+
+extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                                        void* K, void* V, int32_t* pos, int32_t step, void* qwin,
+                                        int32_t* d_len, int32_t len_max_host, void* out,
+                                        void* workspace, void* stream) {
+  if (!ctx || !q || !K || !V || !pos || !qwin || !d_len || !out || step < 0) return GKV_ERR_INVALID_ARG;
+  if ((k_new == nullptr) != (v_new == nullptr)) return GKV_ERR_INVALID_ARG;
+  if (!workspace) return GKV_ERR_WORKSPACE;
+  gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
+  if (st != GKV_OK) return st;
+  AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_len, out, gkv_carve_workspace(ctx, workspace), 1};
+  GkvLaunch ln{ctx, GKV_K_ATTEND, (hipStream_t)stream};
+  if (use_mfma_attend(ctx)) {
+    a.splits = gkv_effective_splits(ctx);
+    return hip_status(gkv_launch_attend_mfma(ln, ctx->dims, a));
+  }
+  return hip_status(gkv_launch_attend_generic(ln, ctx->dims, ctx->cfg.dtype, a));
+}
+
+extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_len,
+                                       int32_t step, int32_t len_max_host, float* S,
+                                       void* workspace, void* stream) {
+  (void)workspace;
+  if (!ctx || !qwin || !K || !d_len || !S || step < 0) return GKV_ERR_INVALID_ARG;
+  gkv_status st = check_len(ctx, len_max_host, false);
+  if (st != GKV_OK) return st;
+  ScoreArgs a{qwin, K, d_len, step, S};
+  GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
+  if (use_mfma_score(ctx)) return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
+  return hip_status(gkv_launch_score_generic(ln, ctx->dims, ctx->cfg.dtype, a));
+}
+
+extern "C" gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
+                                        const int32_t* d_n_hist, const int32_t* d_len,
+                                        int32_t len_max_host, float* F_out, void* stream) {
+  if (!ctx || !S || !F_hist || !d_n_hist || !d_len || !F_out) return GKV_ERR_INVALID_ARG;
+  gkv_status st = check_len(ctx, len_max_host, false);
+  if (st != GKV_OK) return st;
+  GkvLaunch ln{ctx, GKV_K_GLOBAL, (hipStream_t)stream};
+  return hip_status(gkv_launch_global_update(ln, ctx->dims, S, F_hist, d_n_hist, d_len, F_out));
+}
+
+extern "C" gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_len,
+                                      int32_t len_max_host, int32_t* keep_idx, void* workspace, void* stream) {
+  (void)workspace;
+  if (!ctx || !F || !d_len || !keep_idx) return GKV_ERR_INVALID_ARG;
+  gkv_status st = check_len(ctx, len_max_host, false);
+  if (st != GKV_OK) return st;
+  GkvLaunch ln{ctx, GKV_K_TOPK, (hipStream_t)stream};
+  return hip_status(gkv_launch_select_topk(ln, ctx->dims, F, d_len, keep_idx));
+}
+
+extern "C" gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
+                                  float* F_hist, int32_t* pos, int32_t* d_len, int32_t* d_n_hist,
+                                  void* workspace, void* stream) {
+  (void)workspace;
+  if (!ctx || !keep_idx || !F || !K || !V || !F_hist || !pos || !d_len || !d_n_hist) return GKV_ERR_INVALID_ARG;
+  if (F == F_hist) return GKV_ERR_INVALID_ARG;
+  GkvLaunch ln{ctx, GKV_K_COMPACT, (hipStream_t)stream};
+  return hip_status(gkv_launch_compact(ln, ctx->dims, ctx->esz, keep_idx, F, K, V, F_hist, pos, d_len, d_n_hist));
+}
+
+extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
+                                int32_t* d_len, int32_t* d_n_hist, int32_t step, int32_t len_max_host,
+                                float* S, float* F, int32_t* keep_idx, void* workspace, void* stream) {
+  if (!ctx || !qwin || !K || !V || !F_hist || !pos || !d_len || !d_n_hist || !S || !F || !keep_idx || step < 0)
+    return GKV_ERR_INVALID_ARG;
+  if (F == F_hist) return GKV_ERR_INVALID_ARG;
+  gkv_status st = check_len(ctx, len_max_host, false);
+  if (st != GKV_OK) return st;
+  st = gkv_score_window(ctx, qwin, K, d_len, step, len_max_host, S, workspace, stream);
+  if (st != GKV_OK) return st;
+  st = gkv_global_update(ctx, S, F_hist, d_n_hist, d_len, len_max_host, F, stream);
+  if (st != GKV_OK) return st;
+  st = gkv_select_topk(ctx, F, d_len, len_max_host, keep_idx, workspace, stream);
+  if (st != GKV_OK) return st;
+  return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_len, d_n_hist, workspace, stream);
+}
+
+// ---- profiling API ------------------------------------------------------------------------------
+extern "C" gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on) {
+  if (!ctx || !ctx->prof) return GKV_ERR_INVALID_ARG;
+  ctx->prof->on = on != 0;
+  return GKV_OK;
+}
+extern "C" gkv_status gkv_profile_read(gkv_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches) {
+  if (!ctx || !ctx->prof || kernel_id < 0 || kernel_id >= GKV_K_COUNT) return GKV_ERR_INVALID_ARG;
+  profile_drain(ctx->prof, kernel_id);
+  if (total_ms) *total_ms = ctx->prof->done_ms[kernel_id];
+  if (launches) *launches = ctx->prof->done_n[kernel_id];
+  return GKV_OK;
+}
+extern "C" gkv_status gkv_profile_reset(gkv_ctx* ctx) {
+  if (!ctx || !ctx->prof) return GKV_ERR_INVALID_ARG;
+  for (int k = 0; k < GKV_K_COUNT; ++k) {
+    profile_drain(ctx->prof, k);
+    ctx->prof->done_ms[k] = 0;
+    ctx->prof->done_n[k] = 0;
+  }
+  return GKV_OK;
+}

@@ -1,0 +1,158 @@
+// Internal declarations shared by the C-ABI layer and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gkv.h"
+
+#define GKV_WAVE 64
+
+// Dimensions every kernel needs, passed by value.
+struct GkvDims {
+  int32_t L, B, Hq, Hkv, d, g;
+  int32_t b, w, s, cap;
+  int32_t combine;
+  float alpha;
+  float scale;   // softmax scale of Eq. 1
+};
+
+struct GkvProfile;   // event pools, defined in gkv_api.hip
+
+struct gkv_ctx {
+  gkv_config cfg;
+  GkvDims dims;
+  int32_t esz;            // bytes per element
+  int32_t attend_splits;  // 0 = automatic
+  int32_t force_generic;
+  bool mfma_ok;           // bf16, d == 128, g <= 16, w % 16 == 0
+  GkvProfile* prof;
+};
+
+// Workspace layout (bytes from the base):
+//   [0, 4*L*B)                      len tickets (int32, self-resetting)
+//   [.., + 4*units)                 split tickets (int32, self-resetting)
+//   [.., + 4*units*splits*g*(d+2))  split-K partials (float)
+struct GkvWorkspace {
+  int32_t* len_ticket;
+  int32_t* split_ticket;
+  float* partials;
+};
+
+static inline size_t gkv_align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int gkv_effective_splits(const gkv_ctx* ctx);
+GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base);
+
+// Launch record for profiling: the wrappers call this instead of <<< >>>.
+struct GkvLaunch {
+  gkv_ctx* ctx;
+  int kernel_id;
+  hipStream_t stream;
+};
+
+// ---- launch wrappers implemented in the kernel files -------------------------------------
+struct AttendArgs {
+  const void* q; const void* k_new; const void* v_new;
+  void* K; void* V; int32_t* pos; int32_t step; void* qwin; int32_t* d_len; void* out;
+  GkvWorkspace ws; int32_t splits;
+};
+hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
+hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);
+
+struct ScoreArgs {
+  const void* qwin; const void* K; const int32_t* d_len; int32_t step; float* S;
+};
+hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a);
+hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a);
+
+hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
+                                    const float* F_hist, const int32_t* d_n_hist,
+                                    const int32_t* d_len, float* F_out);
+hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
+                                  const int32_t* d_len, int32_t* keep_idx);
+hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
+                              const float* F, void* K, void* V, float* F_hist, int32_t* pos,
+                              int32_t* d_len, int32_t* d_n_hist);
+hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n);
+
+// Event bracketing for profiling (gkv_api.hip).  Returns the events to pass to
+// hipExtLaunchKernelGGL, or nulls when profiling is off.
+void gkv_profile_events(const GkvLaunch& ln, hipEvent_t* start, hipEvent_t* stop);
+
+// ---- device helpers ------------------------------------------------------------------------
+#ifdef __HIPCC__
+#include <hip/hip_ext.h>
+
+template <typename... Args, typename F = void (*)(Args...)>
+static inline hipError_t gkv_launch(const GkvLaunch& ln, F kernel, dim3 grid, dim3 block,
+                                    size_t shmem, Args... args) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  gkv_profile_events(ln, &e0, &e1);
+  if (e0) {
+    hipExtLaunchKernelGGL(kernel, grid, block, shmem, ln.stream, e0, e1, 0, args...);
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, shmem, ln.stream, args...);
+  }
+  return hipGetLastError();
+}
+
+// Element offset of (row n, channel c) in one KV head's tiled K block; EPC = elements per 16 B.
+template <int EPC>
+__device__ __forceinline__ int k_tiled_offset(int n, int c, int d) {
+  return (n >> 4) * 16 * d + (c / EPC) * (16 * EPC) + (n & 15) * EPC + (c % EPC);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {   // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int EPC = 4;
+  __device__ static __forceinline__ float ld(const float* p) { return *p; }
+  __device__ static __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {     // bf16 bit patterns
+  static constexpr int EPC = 8;
+  __device__ static __forceinline__ float ld(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  __device__ static __forceinline__ void st(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
+};
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+// Block-wide reductions over blockDim.x = 256 threads; `red` is 8 floats of LDS.  The result is
+// the same in every thread and independent of scheduling (fixed combination order).
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = fmaxf(r, red[i]);
+  return r;
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r += red[i];
+  return r;
+}
+#endif  // __HIPCC__

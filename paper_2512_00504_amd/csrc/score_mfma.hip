@@ -1,0 +1,206 @@
+// Local score of the observation window on the matrix cores: bf16, head_dim 128,
+// w a multiple of 16, group sizes instantiated below.
+//
+// One workgroup (NW wavefronts) per unit.  The window queries of the group's G heads are
+// staged in LDS once, in window-row order.  A wavefront takes 16-key tiles of K (one 1 KiB
+// contiguous load per 32 channels, thanks to the tiled K layout) and for every (head, block
+// of 16 window rows) computes logits^T[key, row] with 4 MFMA 16x16x32.
+//   pass 1: exact row statistics (max, sum of exp) of Eq. 1 over the keys each row saw;
+//   pass 2: logits again, p = exp(z - max)/sum, running max over the heads in registers
+//           (group max-reduce), then the sum over the 16 lanes that hold the window rows
+//           (Eq. 2).  Only S leaves the chip; the [g, w, l] matrix never exists in memory.
+#include "gkv_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128;
+constexpr int ROW_BYTES = D * 2;
+constexpr int TILE_BYTES = 16 * ROW_BYTES;
+constexpr int QSTR = ROW_BYTES + 16;       // padded LDS row of a staged query (bank spread)
+
+__device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float redM[NW*G*w]; float redS[NW*G*w]
+template <int NW, int G, int WT>
+__global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, kb = lane >> 4;
+  const int unit = blockIdx.x, j = unit % dm.Hkv, lb = unit / dm.Hkv;
+  const int cap = dm.cap;
+  constexpr int W = 16 * WT;
+  constexpr int ROWS = G * W;
+
+  const int l = a.d_len[lb];
+  if (l <= dm.b || l > cap) return;
+  const int cc = l - W;                     // number of candidates
+
+  char* qs = smem_raw;
+  float* rowM = (float*)(qs + ROWS * QSTR);
+  float* rowZ = rowM + ROWS;
+  float* redM = rowZ + ROWS;
+  float* redS = redM + NW * ROWS;
+
+  // stage the window queries: LDS row h*W + k holds head h, window row k (k-th oldest)
+  for (int x = tid; x < ROWS * 16; x += NW * 64) {
+    const int row = x >> 4, ch = x & 15;
+    const int h = row / W, k = row % W;
+    const int t_row = a.step - W + 1 + k;
+    const int slot = ((t_row % W) + W) % W;
+    const size_t head = (size_t)lb * dm.Hq + j * G + h;
+    *(u32x4*)(qs + row * QSTR + ch * 16) =
+        ld16((const char*)a.qwin + (head * W + slot) * (size_t)ROW_BYTES + ch * 16);
+  }
+  __syncthreads();
+
+  const char* Kh = (const char*)a.K + (size_t)unit * cap * ROW_BYTES;
+  const float scale = dm.scale;
+  const int n_tiles = (l + 15) >> 4;
+
+  // ---- pass 1: row max and row sum over the keys visible to each window row -----------------
+  float rm[G][WT], rs[G][WT];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int nt = 0; nt < WT; ++nt) { rm[h][nt] = -1e30f; rs[h][nt] = 0.f; }
+
+  for (int T = wave; T < n_tiles; T += NW) {
+    u32x4 kA[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kA[c] = ld16(Kh + (size_t)T * TILE_BYTES + c * 1024 + lane * 16);
+    const int key_base = 16 * T + 4 * kb;
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int nt = 0; nt < WT; ++nt) {
+        const char* qrow = qs + (h * W + 16 * nt + r) * QSTR;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[c]),
+                                                        as_bf16x8(*(const u32x4*)(qrow + (4 * c + kb) * 16)),
+                                                        acc, 0, 0, 0);
+        const int last_vis = cc + 16 * nt + r;              // row k sees keys [0, cc + k]
+        float z[4];
+        float tm = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          z[e] = (key_base + e <= last_vis) ? acc[e] * scale : -INFINITY;
+          tm = fmaxf(tm, z[e]);
+        }
+        const float mnew = fmaxf(rm[h][nt], tm);
+        float sum = rs[h][nt] * expf(rm[h][nt] - mnew);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += expf(z[e] - mnew);
+        rm[h][nt] = mnew;
+        rs[h][nt] = sum;
+      }
+  }
+  // merge the 4 lanes of a row, then the wavefronts
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int nt = 0; nt < WT; ++nt) {
+      float m = rm[h][nt];
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      float s = rs[h][nt] * expf(rm[h][nt] - m);
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (kb == 0) {
+        redM[wave * ROWS + h * W + 16 * nt + r] = m;
+        redS[wave * ROWS + h * W + 16 * nt + r] = s;
+      }
+    }
+  __syncthreads();
+  for (int x = tid; x < ROWS; x += NW * 64) {
+    float M = redM[x];
+#pragma unroll
+    for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, redM[wv * ROWS + x]);
+    float Z = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < NW; ++wv) Z += redS[wv * ROWS + x] * expf(redM[wv * ROWS + x] - M);
+    rowM[x] = M;
+    rowZ[x] = Z;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int nt = 0; nt < WT; ++nt) {
+      rm[h][nt] = rowM[h * W + 16 * nt + r];
+      rs[h][nt] = rowZ[h * W + 16 * nt + r];
+    }
+
+  // ---- pass 2: probabilities, max over heads, mean over window rows -------------------------
+  float* So = a.S + (size_t)unit * cap;
+  const int cand_tiles = (cc + 15) >> 4;
+  const float wf = (float)W;
+  for (int T = wave; T < cand_tiles; T += NW) {
+    u32x4 kA[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kA[c] = ld16(Kh + (size_t)T * TILE_BYTES + c * 1024 + lane * 16);
+    f32x4 tot = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < WT; ++nt) {
+      f32x4 amax = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const char* qrow = qs + (h * W + 16 * nt + r) * QSTR;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[c]),
+                                                        as_bf16x8(*(const u32x4*)(qrow + (4 * c + kb) * 16)),
+                                                        acc, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          // candidates are visible to every window row; keys >= cc are discarded below
+          const float p = expf(fminf(acc[e] * scale - rm[h][nt], 0.f)) / rs[h][nt];
+          amax[e] = fmaxf(amax[e], p);
+        }
+      }
+      tot += amax;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float v = tot[e];
+      v += __shfl_xor(v, 1);
+      v += __shfl_xor(v, 2);
+      v += __shfl_xor(v, 4);
+      v += __shfl_xor(v, 8);
+      const int key = 16 * T + 4 * kb + e;
+      if (r == 0 && key < cc) So[key] = v / wf;
+    }
+  }
+}
+
+template <int G, int WT>
+hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
+  constexpr int NW = 4;
+  constexpr int ROWS = G * 16 * WT;
+  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, score_mfma_kernel<NW, G, WT>, dim3(units), dim3(NW * 64), shmem, dm, a);
+}
+
+}  // namespace
+
+bool gkv_score_mfma_supported(int g, int w) {
+  const bool g_ok = (g == 1 || g == 2 || g == 4 || g == 5 || g == 7 || g == 8);
+  return g_ok && (w == 16 || w == 32);
+}
+
+hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
+  const int wt = dm.w / 16;
+#define GKV_CASE(G_)                                                        \
+  if (dm.g == G_) return wt == 1 ? launch<G_, 1>(ln, dm, a) : launch<G_, 2>(ln, dm, a);
+  GKV_CASE(1) GKV_CASE(2) GKV_CASE(4) GKV_CASE(5) GKV_CASE(7) GKV_CASE(8)
+#undef GKV_CASE
+  return hipErrorInvalidValue;
+}

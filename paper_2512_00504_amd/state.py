@@ -1,0 +1,101 @@
+"""Device buffers for one decode job, allocated through torch, plus the K-layout
+permutations.  No arithmetic of the method lives here: each method below is one
+call into the C ABI."""
+from __future__ import annotations
+
+import torch
+
+from .binding import Context, GkvConfig, make_config
+
+_TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
+
+
+def k_rows_to_tiled(K_rows: torch.Tensor) -> torch.Tensor:
+    """[..., cap, d] row-major -> the library's tiled K layout (same shape, permuted storage)."""
+    *lead, cap, d = K_rows.shape
+    epc = 16 // K_rows.element_size()
+    t = K_rows.reshape(*lead, cap // 16, 16, d // epc, epc)
+    n = len(lead)
+    t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
+    return t.reshape(*lead, cap, d)
+
+
+def k_tiled_to_rows(K_tiled: torch.Tensor) -> torch.Tensor:
+    """Inverse of k_rows_to_tiled."""
+    *lead, cap, d = K_tiled.shape
+    epc = 16 // K_tiled.element_size()
+    t = K_tiled.reshape(*lead, cap // 16, d // epc, 16, epc)
+    n = len(lead)
+    t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
+    return t.reshape(*lead, cap, d)
+
+
+class DecodeState:
+    """All device state of the path for L layers x B sequences."""
+
+    def __init__(self, cfg: GkvConfig, device="cuda:0", params=None):
+        self.cfg = cfg
+        self.ctx = Context(cfg)
+        for name, val in (params or {}).items():
+            self.ctx.set_param(name, val)
+        L, B, Hq, Hkv, d = cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+        cap, w, b = cfg.capacity, cfg.window, cfg.budget
+        dt = _TORCH_DTYPE[cfg.dtype]
+        dev = torch.device(device)
+        self.device = dev
+        z = lambda *s, dtype: torch.zeros(*s, dtype=dtype, device=dev)
+        self.K = z(L, B, Hkv, cap, d, dtype=dt)          # tiled layout
+        self.V = z(L, B, Hkv, cap, d, dtype=dt)
+        self.pos = torch.full((L, B, Hkv, cap), -1, dtype=torch.int32, device=dev)
+        self.qwin = z(L, B, Hq, w, d, dtype=dt)
+        self.d_len = z(L, B, dtype=torch.int32)
+        self.d_n_hist = z(L, B, dtype=torch.int32)
+        self.F_hist = z(L, B, Hkv, cap, dtype=torch.float32)
+        self.S = z(L, B, Hkv, cap, dtype=torch.float32)
+        self.F = z(L, B, Hkv, cap, dtype=torch.float32)
+        self.keep_idx = z(L, B, Hkv, b - w, dtype=torch.int32)
+        self.out = z(L, B, Hq, d, dtype=dt)
+        self.workspace = torch.zeros(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
+        self.ctx.workspace_init(self.workspace)
+        self.len_host = 0          # host mirror of the (uniform) length, for launch sizing only
+
+    @classmethod
+    def from_workload(cls, wl, device="cuda:0", params=None, **over):
+        kw = dict(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                  head_dim=wl.head_dim, budget=wl.budget, window=wl.window, interval=wl.interval,
+                  capacity=wl.capacity, dtype=wl.dtype, combine=wl.combine, alpha=wl.alpha)
+        kw.update(over)
+        return cls(make_config(**kw), device=device, params=params)
+
+    # one call each -------------------------------------------------------------------------
+    def attend_decode(self, q, k_new, v_new, step):
+        self.ctx.attend_decode(q, k_new, v_new, self.K, self.V, self.pos, step, self.qwin, self.d_len,
+                               self.len_host, self.out, self.workspace)
+        if k_new is not None:
+            self.len_host += 1
+        return self.out
+
+    def score_window(self, step):
+        self.ctx.score_window(self.qwin, self.K, self.d_len, step, self.len_host, self.S, self.workspace)
+
+    def global_update(self):
+        self.ctx.global_update(self.S, self.F_hist, self.d_n_hist, self.d_len, self.len_host, self.F)
+
+    def select_topk(self):
+        self.ctx.select_topk(self.F, self.d_len, self.len_host, self.keep_idx, self.workspace)
+
+    def compact(self):
+        self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_len,
+                         self.d_n_hist, self.workspace)
+        if self.len_host > self.cfg.budget:
+            self.len_host = self.cfg.budget
+
+    def evict(self, step):
+        self.ctx.evict(self.qwin, self.K, self.V, self.F_hist, self.pos, self.d_len, self.d_n_hist, step,
+                       self.len_host, self.S, self.F, self.keep_idx, self.workspace)
+        if self.len_host > self.cfg.budget:
+            self.len_host = self.cfg.budget
+
+    def is_trigger(self, step) -> bool:
+        """Host-side trigger: compression after every s generated tokens once above the budget."""
+        return (step + 1) % self.cfg.interval == 0 and self.len_host > self.cfg.budget

@@ -1,0 +1,260 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
+seeded inputs.  Integer results (kept indices, positions, cache rows) bit-exact up to the
+tolerated-swap rule; outputs within 1e-5 relative (fp32) / 2e-2 absolute (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from gkv_traces import CONFIGS
+from oracle import gkv_oracle as O
+from paper_2512_00504_amd import make_config
+from paper_2512_00504_amd.state import DecodeState, k_rows_to_tiled, k_tiled_to_rows
+
+from parity_utils import check_keep, check_scores, run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ whole-path parity ------
+def test_cfg1_tiny_full_trace_fp32():
+    wl = CONFIGS["cfg1_tiny"]
+    _say("cfg1 tiny fp32, 256 steps")
+    st = run_parity(wl, wl.n_steps)
+    assert st["events"] == 12 and st["swaps"] == 0
+    _say(f"  max out err {st['max_out_err']:.2e}")
+
+
+def test_cfg1_fused_evict_entry_point():
+    wl = CONFIGS["cfg1_tiny"]
+    st = run_parity(wl, 128, fused_evict=True)
+    assert st["events"] == 4
+
+
+@pytest.mark.parametrize("form", ["avg", "sum"])
+def test_cfg1_other_combine_forms(form):
+    wl = CONFIGS["cfg1_tiny"].with_(combine=form, alpha=0.9)
+    st = run_parity(wl, 160)
+    assert st["events"] == 6
+
+
+def test_cfg1_shape_in_bf16_generic_kernels():
+    # bf16 with d = 64 is not covered by the matrix-core kernels: exercises the generic bf16 path
+    wl = CONFIGS["cfg1_tiny"].with_(dtype="bf16", seed=11)
+    st = run_parity(wl, 160)
+    assert st["events"] == 6
+
+
+def test_cfg2_single_layer_full_trace():
+    wl = CONFIGS["cfg2_single_layer"]
+    _say("cfg2 single layer bf16, 4096 steps (split-K attend, MFMA score)")
+    st = run_parity(wl, wl.n_steps, check_state_every_event=False)
+    assert st["events"] == 28
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+def test_cfg2_generic_kernels_match_too():
+    wl = CONFIGS["cfg2_single_layer"]
+    st = run_parity(wl, 896, params={"force_generic": 1}, check_state_every_event=False)
+    assert st["events"] == 3
+
+
+@pytest.mark.parametrize("splits", [1, 3, 5])
+def test_cfg2_split_counts(splits):
+    wl = CONFIGS["cfg2_single_layer"]
+    st = run_parity(wl, 768, params={"attend_splits": splits}, check_state_every_event=False)
+    assert st["events"] == 2
+
+
+def test_cfg3_shape_small_batch_many_layers():
+    # 28-layer head shape, 3 layers x 2 sequences so that every unit is checked
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=3, batch=2)
+    st = run_parity(wl, 1024, check_state_every_event=False)
+    assert st["events"] == 4
+
+
+def test_cfg3_full_size_sampled_units():
+    # the launch configuration the benchmark times: all 896 units on the GPU, the oracle on a
+    # sample of (layer, sequence) pairs that covers first/last layer and sequence
+    wl = CONFIGS["cfg3_28layer_b512"]
+    pairs = [(0, 0), (0, 7), (13, 3), (27, 0), (27, 7)]
+    _say("cfg3 full size, 768 steps, 5 sampled pairs (20 units)")
+    st = run_parity(wl, 768, pairs=pairs, check_state_every_event=False)
+    assert st["events"] == 2
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+@pytest.mark.parametrize("budget,steps", [(1024, 1408), (2048, 2432)])
+def test_cfg4_budgets(budget, steps):
+    wl = CONFIGS["cfg4_b512"].with_(n_layers=1, batch=2, budget=budget)
+    st = run_parity(wl, steps, check_state_every_event=False)
+    assert st["events"] == 3
+
+
+def test_cfg4_local_only_leg():
+    wl = CONFIGS["cfg4_b512_local"].with_(n_layers=2, batch=1)
+    st = run_parity(wl, 1024, check_state_every_event=False)
+    assert st["events"] == 4
+    # alpha = 0: the recorded history never matters, so the max form with zeroed n_hist agrees
+    for orc in st["oracles"].values():
+        for ev in orc.events:
+            np.testing.assert_array_equal(O.select_topk(ev["S"], wl.budget - wl.window), ev["keep"])
+
+
+def test_cfg5_shape_heavy_tailed_keys():
+    wl = CONFIGS["cfg5_large_batch"].with_(n_layers=1, batch=2)
+    _say("cfg5 shape (g=5, w=32, s=64, b=1024, Student-t keys), 1216 steps")
+    st = run_parity(wl, 1216, check_state_every_event=False)
+    assert st["events"] == 3
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+# ------------------------------------------------------------------ single calls, edge cases
+def _state(dtype="f32", **kw):
+    base = dict(n_layers=1, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, budget=32, window=4,
+                interval=8, capacity=64, dtype=dtype)
+    base.update(kw)
+    return DecodeState(make_config(**base))
+
+
+def test_attend_ragged_lengths_and_empty_append():
+    st = _state()
+    g = torch.Generator().manual_seed(1)
+    K = torch.randn(1, 2, 2, 64, 64, generator=g); V = torch.randn(1, 2, 2, 64, 64, generator=g)
+    q = torch.randn(1, 2, 4, 64, generator=g)
+    st.K.copy_(k_rows_to_tiled(K)); st.V.copy_(V)
+    st.d_len.copy_(torch.tensor([[5, 37]], dtype=torch.int32)); st.len_host = 37
+    out = st.attend_decode(q.cuda(), None, None, 3).double().cpu().numpy()
+    assert st.d_len.cpu().tolist() == [[5, 37]]                   # no append: lengths unchanged
+    for b, n in enumerate((5, 37)):
+        ref = O.attend(q[0, b].numpy(), K[0, b].numpy(), V[0, b].numpy(), n)
+        np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=1e-5 * np.abs(ref).max())
+    # window ring slot 3 now holds q
+    np.testing.assert_array_equal(st.qwin[0, :, :, 3].cpu().numpy(), q[0].numpy())
+
+
+def test_attend_rejects_bad_arguments():
+    from paper_2512_00504_amd import GkvError
+    st = _state()
+    q = torch.zeros(1, 2, 4, 64, device="cuda")
+    kv = torch.zeros(1, 2, 2, 64, device="cuda")
+    st.len_host = 64                                              # would overflow the capacity
+    with pytest.raises(GkvError) as e:
+        st.attend_decode(q, kv, kv, 0)
+    assert e.value.status == 6
+    st.len_host = 0
+    with pytest.raises(GkvError) as e:
+        st.ctx.attend_decode(q, kv, None, st.K, st.V, st.pos, 0, st.qwin, st.d_len, 0, st.out, st.workspace)
+    assert e.value.status == 1
+    with pytest.raises(GkvError) as e:
+        st.ctx.attend_decode(q, kv, kv, st.K, st.V, st.pos, 0, st.qwin, st.d_len, 0, st.out, None)
+    assert e.value.status == 3
+
+
+def test_score_window_closed_form_equal_keys():
+    # all keys equal: S[n] = (1/w) sum_k 1/(c+k+1) for every candidate
+    for dtype, kw in (("f32", {}), ("bf16", dict(head_dim=128, n_q_heads=8, n_kv_heads=2, window=16,
+                                                  interval=16, budget=48, capacity=96))):
+        st = _state(dtype, **kw)
+        w, cap = st.cfg.window, st.cfg.capacity
+        l = st.cfg.budget + st.cfg.interval - 3
+        st.K.fill_(0.5)
+        st.qwin.copy_(torch.randn(st.qwin.shape).to(st.qwin.dtype))
+        st.d_len.fill_(l); st.len_host = l
+        st.score_window(step=l - 1)
+        c = l - w
+        expect = sum(1.0 / (c + k + 1) for k in range(w)) / w
+        S = st.S[..., :c].double().cpu().numpy()
+        np.testing.assert_allclose(S, expect, rtol=2e-6)
+
+
+def test_eviction_is_a_noop_at_or_below_budget():
+    st = _state()
+    st.d_len.copy_(torch.tensor([[32, 40]], dtype=torch.int32)); st.len_host = 40
+    st.K.copy_(torch.randn(st.K.shape)); st.V.copy_(torch.randn(st.V.shape))
+    st.qwin.copy_(torch.randn(st.qwin.shape))
+    K0, V0 = st.K.clone(), st.V.clone()
+    st.evict(step=39)
+    assert st.d_len.cpu().tolist() == [[32, 32]] and st.d_n_hist.cpu().tolist() == [[0, 28]]
+    assert torch.equal(st.K[0, 0], K0[0, 0]) and torch.equal(st.V[0, 0], V0[0, 0])     # sequence 0 untouched
+    assert not torch.equal(st.V[0, 1], V0[0, 1])
+
+
+def test_global_update_three_forms_against_oracle():
+    rng = np.random.default_rng(5)
+    for form in ("max", "avg", "sum"):
+        st = _state(combine=form, alpha=0.8)
+        l, w = 40, 4
+        c = l - w
+        S = rng.random((1, 2, 2, 64)).astype(np.float32) ** 3
+        H = rng.random((1, 2, 2, 64)).astype(np.float32)
+        st.S.copy_(torch.from_numpy(S)); st.F_hist.copy_(torch.from_numpy(H))
+        st.d_len.fill_(l); st.len_host = l
+        st.d_n_hist.copy_(torch.tensor([[0, 28]], dtype=torch.int32))
+        st.global_update()
+        F = st.F.cpu().numpy()
+        for b, nh in enumerate((0, 28)):
+            ref = O.global_score(S[0, b].astype(np.float64), H[0, b].astype(np.float64), nh, 0.8, form, n_cand=c)
+            np.testing.assert_allclose(F[0, b, :, :c], ref, rtol=3e-7, atol=1e-30)
+
+
+def test_select_topk_ties_nan_and_brute_force():
+    st = _state()
+    l, w, k = 40, 4, 28
+    c = l - w
+    st.d_len.fill_(l); st.len_host = l
+    rng = np.random.default_rng(6)
+    F = np.zeros((1, 2, 2, 64), np.float32)
+    F[0, 0, 0, :c] = 0.25                                   # all tied: first k indices
+    F[0, 0, 1, :c] = np.round(rng.random(c), 1)            # many ties
+    F[0, 1, 0, :c] = rng.random(c)
+    F[0, 1, 1, :c] = rng.random(c); F[0, 1, 1, 3] = np.nan; F[0, 1, 1, 7] = np.inf; F[0, 1, 1, 9] = -0.0
+    st.F.copy_(torch.from_numpy(F))
+    st.select_topk()
+    keep = st.keep_idx.cpu().numpy()
+    assert keep[0, 0, 0].tolist() == list(range(k))
+    for (b, j) in ((0, 1), (1, 0)):
+        ref = O.select_topk(F[0, b, j, :c][None].astype(np.float64), k)[0]
+        np.testing.assert_array_equal(keep[0, b, j], ref)
+    odd = keep[0, 1, 1]
+    assert len(set(odd.tolist())) == k and odd.min() >= 0 and odd.max() < c and (np.diff(odd) > 0).all()
+    assert 7 in odd.tolist()
+
+
+@pytest.mark.parametrize("pattern", ["front", "back", "alternate", "random"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compact_adversarial_keep_patterns(pattern, dtype):
+    kw = {} if dtype == "f32" else dict(head_dim=128)
+    st = _state(dtype, budget=160, window=8, interval=32, capacity=192, **kw)
+    b, w, l = 160, 8, 192
+    c, k = l - w, b - w
+    rng = np.random.default_rng(7)
+    if pattern == "front":
+        keep = np.arange(c - k, c)
+    elif pattern == "back":
+        keep = np.arange(k)
+    elif pattern == "alternate":
+        keep = np.sort(np.concatenate([np.arange(0, 64, 2), np.arange(64, 64 + k - 32)]))
+    else:
+        keep = np.sort(rng.permutation(c)[:k])
+    keep_all = np.broadcast_to(keep, (1, 2, 2, k)).astype(np.int32).copy()
+    keep_all[0, 1, 1] = np.sort(rng.permutation(c)[:k])
+    K = torch.randn(st.K.shape).to(st.K.dtype); V = torch.randn(st.V.shape).to(st.V.dtype)
+    pos = torch.arange(192, dtype=torch.int32).expand(1, 2, 2, 192).contiguous() + 1000
+    F = torch.rand(1, 2, 2, 192)
+    st.K.copy_(k_rows_to_tiled(K)); st.V.copy_(V); st.pos.copy_(pos); st.F.copy_(F)
+    st.keep_idx.copy_(torch.from_numpy(keep_all))
+    st.d_len.fill_(l); st.len_host = l
+    st.compact()
+    assert st.d_len.cpu().tolist() == [[b, b]] and st.d_n_hist.cpu().tolist() == [[k, k]]
+    Kr = k_tiled_to_rows(st.K).cpu()
+    for bb in range(2):
+        for j in range(2):
+            src = np.concatenate([keep_all[0, bb, j], np.arange(c, l)])
+            assert torch.equal(Kr[0, bb, j, :b], K[0, bb, j, src])
+            assert torch.equal(st.V[0, bb, j, :b].cpu(), V[0, bb, j, src])
+            assert torch.equal(st.pos[0, bb, j, :b].cpu(), pos[0, bb, j, src])
+            assert torch.equal(st.F_hist[0, bb, j, :k].cpu(), F[0, bb, j, keep_all[0, bb, j]])

@@ -1,0 +1,114 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+validates configurations on the host, and its host-side arithmetic (memory accounting, K
+layout offsets) matches the paper's printed numbers and the binding's permutation."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_00504_amd as P
+from paper_2512_00504_amd.state import k_rows_to_tiled, k_tiled_to_rows
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _golden(name):
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                k, v = line.split(":")
+                out[k.strip()] = float(v)
+    return out
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gkv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(gkv_[a-z_0-9]+)\s*\(", header))
+    assert {"gkv_attend_decode", "gkv_score_window", "gkv_global_update", "gkv_select_topk",
+            "gkv_compact"} <= declared
+    lib = ctypes.CDLL(P.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in gkv.h but not exported"
+    assert declared == set(P.EXPORTS)
+
+
+def _cfg(**kw):
+    base = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, head_dim=64, budget=64, window=8,
+                interval=16, capacity=96, dtype="f32")
+    base.update(kw)
+    return P.make_config(**base)
+
+
+def test_create_validates_configuration():
+    ctx = P.Context(_cfg())
+    assert ctx.workspace_bytes() > 0
+    ctx.close()
+    bad = [dict(window=17),                 # w > s
+           dict(window=8, budget=8),        # w >= b
+           dict(n_q_heads=7),               # h_q % h_kv
+           dict(alpha=1.5), dict(alpha=float("nan")),
+           dict(dtype=3), dict(combine=5),
+           dict(capacity=64),               # < b + s
+           dict(capacity=100),              # not a multiple of 32
+           dict(head_dim=62)]
+    for kw in bad:
+        with pytest.raises(P.GkvError):
+            P.Context(_cfg(**kw))
+    lib = P.load_library()
+    assert lib.gkv_create(None, None) == 1
+    assert lib.gkv_status_string(6) == b"cache capacity exceeded"
+
+
+def test_calls_reject_null_pointers_without_a_gpu():
+    ctx = P.Context(_cfg())
+    lib = P.load_library()
+    n = ctypes.c_void_p(None)
+    assert lib.gkv_attend_decode(ctx.h, n, n, n, n, n, n, 0, n, n, 0, n, n, n) == 1
+    assert lib.gkv_score_window(ctx.h, n, n, n, 0, 0, n, n, n) == 1
+    assert lib.gkv_global_update(ctx.h, n, n, n, n, 0, n, n) == 1
+    assert lib.gkv_select_topk(ctx.h, n, n, 0, n, n, n) == 1
+    assert lib.gkv_compact(ctx.h, n, n, n, n, n, n, n, n, n, n) == 1
+    assert lib.gkv_set_param(ctx.h, b"no_such_knob", 1) == 1
+
+
+def test_memory_accounting_reproduces_the_papers_appendix():
+    g = _golden("memory_analysis.txt")
+    GB = float(2 ** 30)
+    # the paper's example: 28 layers, 2 KV heads, d = 128, bf16
+    one = P.make_config(28, 1, 28, 2, 128, 512, 16, 128, 640, "bf16")
+    kv, _ = P.cache_bytes(one, 16384)
+    assert round(kv / GB, 2) == g["full_kv_per_sequence_gb"]
+    full = P.make_config(28, 128, 28, 2, 128, 512, 16, 128, 640, "bf16")
+    kv_full, _ = P.cache_bytes(full, 16384)
+    assert round(kv_full / GB) == g["full_kv_batch128_gb"]
+    for b in (512, 1024, 2048):
+        cfg = P.make_config(28, 128, 28, 2, 128, b, 16, 128, b + 128, "bf16")
+        kv, sc = P.cache_bytes(cfg, b + 128, 2)
+        assert kv / GB == pytest.approx(g[f"compressed_kv_gb_b{b}"], abs=0.011)
+        # savings: exact values are 96.09 / 92.97 / 86.72 %, printed to one decimal
+        assert 100 * (1 - kv / kv_full) == pytest.approx(g[f"saving_percent_b{b}"], abs=0.08)
+        kv_b, sc_b = P.cache_bytes(cfg, b, 2)
+        assert sc_b / kv_b == pytest.approx((b - 16) / (b * 128 * 2))
+        assert sc_b / kv_b == pytest.approx(g["score_fraction_approx"], rel=0.04)
+
+
+def test_k_offset_matches_the_tiling_permutation():
+    for dtype, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+        cfg = _cfg(dtype=dtype, head_dim=64, capacity=96)
+        rows = torch.arange(96 * 64, dtype=torch.float32).reshape(96, 64).to(tdt)      # exact in bf16? use ids below
+        ids = torch.arange(96 * 64, dtype=torch.int32).reshape(96, 64)
+        flat = k_rows_to_tiled(ids.view(tdt) if tdt == torch.float32 else ids.to(torch.int16).view(tdt))
+        flat_ids = (flat.view(torch.int32) if tdt == torch.float32 else flat.view(torch.int16)).reshape(-1)
+        for (r, c) in ((0, 0), (1, 0), (15, 63), (16, 0), (17, 9), (95, 63), (40, 7), (40, 8)):
+            off = P.k_offset(cfg, r, c)
+            assert int(flat_ids[off]) == r * 64 + c
+        back = k_tiled_to_rows(flat)
+        assert torch.equal(back.view(torch.int32) if tdt == torch.float32 else back.view(torch.int16),
+                           ids if tdt == torch.float32 else ids.to(torch.int16))
+    assert P.k_offset(_cfg(), -1, 0) == -1 and P.k_offset(_cfg(), 0, 64) == -1
