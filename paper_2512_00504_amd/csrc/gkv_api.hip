@@ -57,7 +57,7 @@ static gkv_status validate_config(const gkv_config* c) {
   const int esz = c->dtype == GKV_F32 ? 4 : 2;
   const int epc = 16 / esz;
   if (c->head_dim % epc != 0 || c->head_dim > 1024) return GKV_ERR_SHAPE;
-  if (c->capacity < c->budget + c->interval || c->capacity % 32 != 0 || c->capacity > 16384)
+  if (c->capacity < c->budget + c->interval || c->capacity % 32 != 0 || c->capacity > 4096)
     return GKV_ERR_SHAPE;
   const int64_t units = (int64_t)c->n_layers * c->batch * c->n_kv_heads;
   if (units > (1 << 24)) return GKV_ERR_SHAPE;

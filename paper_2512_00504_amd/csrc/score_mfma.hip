@@ -193,7 +193,9 @@ hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
 
 bool gkv_score_mfma_supported(int g, int w) {
   const bool g_ok = (g == 1 || g == 2 || g == 4 || g == 5 || g == 7 || g == 8);
-  return g_ok && (w == 16 || w == 32);
+  if (!g_ok || (w != 16 && w != 32)) return false;
+  const size_t rows = (size_t)g * w;                      // LDS the kernel needs; 64 KiB available
+  return rows * QSTR + sizeof(float) * (2 * rows + 2 * 4 * rows) <= 65536;
 }
 
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
