@@ -1,0 +1,300 @@
+#!/usr/bin/env python3
+"""Benchmark of the G-KV decode/evict hot path on one MI355X.
+
+A "step" is one decode step of the whole path for the whole batch: one
+gkv_attend_decode launch covering every layer, plus, every s steps, one
+compression (gkv_score_window, gkv_global_update, gkv_select_topk,
+gkv_compact).  The timed region is K consecutive steady-state steps (cache
+length cycling b+1 .. b+s) on synthetic inputs that are already resident in
+HBM; it is bracketed by device synchronisation on both sides.
+
+Prints ONE JSON line: metric/value (tokens/s = batch * K / seconds), the
+roofline object of the dominant kernel (attend) from per-launch HIP events
+recorded on the launch stream, and the CPU oracle's rate on a bounded sample.
+"""
+import argparse
+import ctypes
+import json
+import os
+import subprocess
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+
+
+# ------------------------------------------------------------------------------------------------
+# CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
+# ------------------------------------------------------------------------------------------------
+def cpu_worker(workload: str, layer: int, seq: int, seconds: float):
+    """Child process: run the oracle for one (layer, sequence) pair to steady state, then time
+    whole compression cycles (s steps + one event) for about `seconds`."""
+    from threadpoolctl import threadpool_limits
+    import numpy as np  # noqa: F401
+    from gkv_traces import CONFIGS, Trace
+    from oracle import gkv_oracle as O
+    wl = CONFIGS[workload]
+    with threadpool_limits(limits=1):
+        tr = Trace(wl)
+        orc = O.OracleA(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.window, wl.interval,
+                        capacity=wl.capacity, alpha=wl.alpha, form=wl.combine)
+        s = wl.interval
+        pre = ((wl.budget + s - 1) // s + 1) * s
+        q, k, v = tr.unit_steps(layer, seq, 0, pre)
+        for t in range(pre):
+            orc.step(t, q[t], k[t], v[t])
+        t_next, done, elapsed = pre, 0, 0.0
+        while elapsed < seconds:
+            q, k, v = tr.unit_steps(layer, seq, t_next, s)
+            t0 = time.perf_counter()
+            for i in range(s):
+                orc.step(t_next + i, q[i], k[i], v[i])
+            elapsed += time.perf_counter() - t0
+            t_next += s
+            done += s
+    print(json.dumps({"pair_steps": done, "seconds": elapsed, "events": len(orc.events)}))
+
+
+def cpu_baseline(workload: str, seconds: float):
+    from gkv_traces import CONFIGS
+    wl = CONFIGS[workload]
+    n_workers = max(1, min(16, os.cpu_count() or 1, wl.n_layers * wl.batch))
+    procs = []
+    for i in range(n_workers):
+        layer, seq = (i * 7) % wl.n_layers, i % wl.batch
+        procs.append(subprocess.Popen(
+            [sys.executable, os.path.abspath(__file__), "--cpu-worker", workload, str(layer), str(seq), str(seconds)],
+            stdout=subprocess.PIPE, text=True, cwd=ROOT))
+    rate, total_steps = 0.0, 0
+    for p in procs:
+        out, _ = p.communicate()
+        rec = json.loads(out.strip().splitlines()[-1])
+        rate += rec["pair_steps"] / rec["seconds"]            # (layer, sequence)-steps per second
+        total_steps += rec["pair_steps"]
+    # a decoded token needs one step of every layer of its sequence
+    tokens_per_s = rate / wl.n_layers
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": n_workers, "kind": "oracle",
+            "sample": (f"{n_workers} (layer, sequence) pairs of {wl.n_layers * wl.batch}, steady-state "
+                       f"cycles of {wl.interval} steps + 1 compression, {total_steps} pair-steps in "
+                       f"~{seconds:.0f} s per worker, one thread each; scaled by 1/n_layers")}
+
+
+# ------------------------------------------------------------------------------------------------
+def algorithmic_bytes(wl):
+    """Bytes the method must move (per unit): attend at length l: e*d*(2l + 2g + 2);
+    compression at l = b+s: score e*d*(l + g*w) + 4(l-w); update 4(n_hist + l - w);
+    top-k 4(l-w) + 4(b-w); compaction 2*(2*e*d + 8)*m with m <= b rows that move (upper bound m = b)."""
+    e = 4 if wl.dtype == "f32" else 2
+    d, g, b, w, s = wl.head_dim, wl.group, wl.budget, wl.window, wl.interval
+    units = wl.n_units
+    l_mean = b + (s + 1) / 2.0
+    l = b + s
+    return {
+        "attend": units * e * d * (2 * l_mean + 2 * g + 2),
+        "score": units * (e * d * (l + g * w) + 4 * (l - w)),
+        "global": units * 4 * ((b - w) + (l - w)),
+        "topk": units * (4 * (l - w) + 4 * (b - w)),
+        "compact": units * 2 * (2 * e * d + 8) * b,
+    }
+
+
+def read_traffic(workload: str):
+    """HBM bytes per attend launch from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"attend_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1280)
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--workload", default="cfg3_28layer_b512")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--cpu-worker", nargs=4, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS"))
+    args = ap.parse_args()
+
+    if args.cpu_worker:
+        wlname, layer, seq, secs = args.cpu_worker
+        cpu_worker(wlname, int(layer), int(seq), float(secs))
+        return
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    from gkv_traces import CONFIGS, Trace
+    wl = CONFIGS[args.workload]
+
+    # CPU leg first, before this process touches the GPU (children are plain CPU processes)
+    cpu = None
+    if not args.no_cpu_baseline and not args.copy_calibration:
+        cpu = cpu_baseline(args.workload, args.cpu_seconds)
+
+    import torch
+    from paper_2512_00504_amd.state import DecodeState
+    dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
+        return
+
+    s, b = wl.interval, wl.budget
+    K = max(s, (args.steps + s - 1) // s * s)            # whole compression cycles
+    W = max(s, (args.warmup + s - 1) // s * s)
+    preroll = b                                          # tokens placed in the cache before step b
+    params = {}
+    if args.splits:
+        params["attend_splits"] = args.splits
+    if args.tile:
+        params["attend_tile"] = args.tile
+    st = DecodeState.from_workload(wl, device=dev, params=params)
+    tr = Trace(wl)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    lib, h = st.ctx.lib, st.ctx.h
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    pK, pV, ppos, pqwin, plen, pnh = P(st.K), P(st.V), P(st.pos), P(st.qwin), P(st.d_len), P(st.d_n_hist)
+    pout, pws, pFh, pS, pF, pkeep = P(st.out), P(st.workspace), P(st.F_hist), P(st.S), P(st.F), P(st.keep_idx)
+
+    def upload(t0, n):
+        q, k, v = tr.batch_steps(t0, n, workers=8)
+        return [torch.from_numpy(x).to(dt).to(dev) for x in (q, k, v)]
+
+    def run(qd, kd, vd, t0, n):
+        """n decode steps starting at absolute step t0 on pre-uploaded inputs; raw C calls."""
+        qs, ks, vs = qd.stride(0) * qd.element_size(), kd.stride(0) * kd.element_size(), vd.stride(0) * vd.element_size()
+        qb, kb_, vb = qd.data_ptr(), kd.data_ptr(), vd.data_ptr()
+        len_host = st.len_host
+        for i in range(n):
+            t = t0 + i
+            rc = lib.gkv_attend_decode(h, qb + i * qs, kb_ + i * ks, vb + i * vs, pK, pV, ppos, t, pqwin, plen,
+                                       len_host, pout, pws, stream)
+            if rc:
+                raise RuntimeError(f"gkv_attend_decode failed: {rc}")
+            len_host += 1
+            if (t + 1) % s == 0 and len_host > b:
+                rc = lib.gkv_evict(h, pqwin, pK, pV, pFh, ppos, plen, pnh, t, len_host, pS, pF, pkeep, pws, stream)
+                if rc:
+                    raise RuntimeError(f"gkv_evict failed: {rc}")
+                len_host = b
+        st.len_host = len_host
+
+    # The first b tokens are placed in the cache directly: no compression happens before the
+    # cache exceeds the budget, so this is the state b decode steps leave behind, and every
+    # attend launch of this process then runs at a steady-state length b+1 .. b+s.
+    _, k0, v0 = tr.batch_steps(0, b, workers=8)
+    st.load_prefix(torch.from_numpy(k0).to(dev), torch.from_numpy(v0).to(dev))
+    del k0, v0
+    t_abs = b
+    assert b % s == 0 and W >= s, "warm-up must cover one whole compression cycle"
+    for c0 in range(0, W, s):                             # untimed warm-up cycles (first compression)
+        qd, kd, vd = upload(t_abs, s)
+        run(qd, kd, vd, t_abs, s)
+        t_abs += s
+    torch.cuda.synchronize()
+    assert int(st.d_len.max()) == b and int(st.d_len.min()) == b
+
+    chunks = [upload(t_abs + c0, s) for c0 in range(0, K, s)]     # all timed inputs resident in HBM
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall = time.perf_counter()
+    ev0.record()
+    for ci, (qd, kd, vd) in enumerate(chunks):
+        run(qd, kd, vd, t_abs + ci * s, s)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t_wall
+    gpu_s = ev0.elapsed_time(ev1) / 1e3
+    elapsed = max(wall_s, gpu_s)
+    t_abs += K
+
+    # per-kernel durations: same steps again with every launch bracketed by its own HIP events
+    st.ctx.profile_reset()
+    st.ctx.profile_enable(True)
+    for ci, (qd, kd, vd) in enumerate(chunks):
+        run(qd, kd, vd, t_abs + ci * s, s)
+    torch.cuda.synchronize()
+    st.ctx.profile_enable(False)
+    per_kernel = {}
+    for name in ("attend", "score", "global", "topk", "compact"):
+        ms, n = st.ctx.profile_read(name)
+        per_kernel[name] = {"launches": n, "avg_us": (1e3 * ms / n) if n else None}
+
+    # read bandwidth a trivial streaming kernel sustains on this GPU, for context: over a buffer
+    # far larger than any cache, and over one the size of this workload's K+V cache
+    from paper_2512_00504_amd.binding import probe_stream_read
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    ceilings = {}
+    for label, nbytes in (("4GiB", 4 << 30), ("kv_cache_size", int(st.K.numel() * st.K.element_size() * 2))):
+        buf = torch.empty(nbytes // 16 * 16, dtype=torch.uint8, device=dev).fill_(3)
+        for _ in range(3):
+            probe_stream_read(buf, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            probe_stream_read(buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ceilings[label] = {"bytes": buf.numel(), "GBps": buf.numel() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+        del buf
+
+    alg = algorithmic_bytes(wl)
+    att_us = per_kernel["attend"]["avg_us"]
+    achieved = alg["attend"] / (att_us * 1e-6) / 1e9
+    for name in per_kernel:
+        us = per_kernel[name]["avg_us"]
+        per_kernel[name]["algorithmic_MB"] = alg[name] / 1e6
+        per_kernel[name]["GBps"] = (alg[name] / (us * 1e-6) / 1e9) if us else None
+    bytes_per_step = alg["attend"] + (alg["score"] + alg["global"] + alg["topk"] + alg["compact"]) / s
+    tokens_per_s = wl.batch * K / elapsed
+    out = {
+        "metric": "decode tokens/sec through attend+score+evict at budget 512; % HBM roofline"
+                  if b == 512 else f"decode tokens/sec through attend+score+evict at budget {b}",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "n_layers": wl.n_layers, "batch": wl.batch,
+                   "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
+                   "budget": b, "window": wl.window, "interval": s, "alpha": wl.alpha,
+                   "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
+                   "attend_splits": args.splits, "attend_tile": args.tile},
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),
+                     "algorithmic_bytes_per_launch": alg["attend"], "avg_launch_us": att_us},
+        "cpu_baseline": cpu,
+        "whole_step": {"algorithmic_bytes_per_step": bytes_per_step,
+                       "GBps": bytes_per_step * K / elapsed / 1e9,
+                       "hbm_frac": bytes_per_step * K / elapsed / 1e9 / HBM_PEAK_GBS,
+                       "gpu_seconds": gpu_s, "wall_seconds": wall_s},
+        "per_kernel": per_kernel,
+        "stream_read_ceiling": ceilings,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -122,8 +122,9 @@ class Trace:
             out_q.append(q[lo:hi]); out_k.append(k[lo:hi]); out_v.append(v[lo:hi])
         return (np.concatenate(out_q), np.concatenate(out_k), np.concatenate(out_v))
 
-    def batch_steps(self, t0: int, n: int, layers=None, seqs=None):
-        """q [n,L,B,h_q,d], k/v [n,L,B,h_kv,d] (float32, dtype-rounded) for the whole batch."""
+    def batch_steps(self, t0: int, n: int, layers=None, seqs=None, workers: int = 1):
+        """q [n,L,B,h_q,d], k/v [n,L,B,h_kv,d] (float32, dtype-rounded) for the whole batch.
+        `workers` > 1 draws the (layer, sequence) pairs on a thread pool (same values)."""
         cfg = self.cfg
         layers = range(cfg.n_layers) if layers is None else layers
         seqs = range(cfg.batch) if seqs is None else seqs
@@ -131,7 +132,19 @@ class Trace:
         q = np.empty((n, L, B, cfg.n_q_heads, cfg.head_dim), np.float32)
         k = np.empty((n, L, B, cfg.n_kv_heads, cfg.head_dim), np.float32)
         v = np.empty_like(k)
-        for li, layer in enumerate(layers):
-            for bi, seq in enumerate(seqs):
-                q[:, li, bi], k[:, li, bi], v[:, li, bi] = self.unit_steps(layer, seq, t0, n)
+        for layer in layers:
+            self.static(layer)
+
+        def fill(args):
+            li, layer, bi, seq = args
+            q[:, li, bi], k[:, li, bi], v[:, li, bi] = self.unit_steps(layer, seq, t0, n)
+
+        jobs = [(li, layer, bi, seq) for li, layer in enumerate(layers) for bi, seq in enumerate(seqs)]
+        if workers > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(workers) as ex:
+                list(ex.map(fill, jobs))
+        else:
+            for j in jobs:
+                fill(j)
         return q, k, v

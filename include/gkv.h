@@ -96,8 +96,10 @@ gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_el
                            size_t* kv_bytes, size_t* score_bytes);
 int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel);
 
-/* Tuning knobs (host only): "attend_splits" (0 = automatic), "force_generic"
- * (1 = use the plain vector-ALU kernels even where matrix-core kernels exist). */
+/* Tuning knobs (host only): "attend_splits" (0 = automatic; set before
+ * gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
+ * the matrix-core attend kernel), "force_generic" (1 = use the plain vector-ALU
+ * kernels even where matrix-core kernels exist). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*
@@ -177,6 +179,13 @@ typedef enum {
 gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on);
 gkv_status gkv_profile_read(gkv_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches);
 gkv_status gkv_profile_reset(gkv_ctx* ctx);
+
+/*
+ * Measurement aid, not part of the method: enqueues a plain streaming read of `bytes` bytes
+ * of device memory at `src` (16-byte loads, 2048 workgroups); `sink` is 4 bytes of device
+ * memory.  Timing it gives the read bandwidth the GPU sustains, a ceiling to compare with.
+ */
+gkv_status gkv_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -12,7 +12,7 @@ import os
 from ctypes import POINTER, byref, c_char_p, c_double, c_float, c_int32, c_int64, c_size_t, c_void_p
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgkv.so")
+LIB_PATH = os.environ.get("GKV_LIB_PATH") or os.path.join(_HERE, "libgkv.so")
 
 GKV_F32, GKV_BF16 = 0, 1
 GKV_COMBINE = {"max": 0, "avg": 1, "sum": 2}
@@ -22,7 +22,7 @@ EXPORTS = [
     "gkv_create", "gkv_destroy", "gkv_status_string", "gkv_workspace_bytes", "gkv_workspace_init",
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
-    "gkv_profile_read", "gkv_profile_reset",
+    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read",
 ]
 
 
@@ -71,6 +71,7 @@ def load_library():
     lib.gkv_profile_enable.argtypes = [vp, i32]
     lib.gkv_profile_read.argtypes = [vp, i32, POINTER(c_double), POINTER(c_int64)]
     lib.gkv_profile_reset.argtypes = [vp]
+    lib.gkv_probe_stream_read.argtypes = [vp, c_size_t, vp, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("gkv_destroy", "gkv_status_string", "gkv_k_offset"):
@@ -176,6 +177,14 @@ class Context:
         ms, n = c_double(), c_int64()
         self._check(self.lib.gkv_profile_read(self.h, KERNEL_IDS[kernel], byref(ms), byref(n)), "gkv_profile_read")
         return ms.value, n.value
+
+
+def probe_stream_read(src, sink):
+    """Enqueue one streaming read of the whole tensor `src` (measurement aid)."""
+    lib = load_library()
+    st = lib.gkv_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream())
+    if st != 0:
+        raise GkvError(st, "gkv_probe_stream_read")
 
 
 def cache_bytes(cfg: GkvConfig, rows: int, score_elem_bytes: int = 4):

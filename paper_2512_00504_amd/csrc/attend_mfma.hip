@@ -22,12 +22,31 @@
 // row): the lanes that would hold row `len` take them from k_new / v_new instead.
 #include "gkv_internal.h"
 
+#ifndef GKV_STREAM_NT
+#define GKV_STREAM_NT 1
+#endif
+#ifndef GKV_EXP_NOCOMPUTE
+#define GKV_EXP_NOCOMPUTE 0      // experiment: skip the arithmetic, keep the loads
+#endif
+#ifndef GKV_EXP_NOEPI
+#define GKV_EXP_NOEPI 0          // experiment: skip merge, output and append
+#endif
+#ifndef GKV_EXP_NOLEN
+#define GKV_EXP_NOLEN 0          // experiment: do not read the length or take the ticket
+#endif
+#ifndef GKV_EXP_NOPV
+#define GKV_EXP_NOPV 0           // experiment: skip the P.V product
+#endif
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int ROW_BYTES = D * 2;          // 256
@@ -36,10 +55,182 @@ constexpr int OSTR = D + 4;               // padded LDS row of the per-wave part
 constexpr int PSTR = D + 2;               // split-K partial: o[128], m, l
 
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
+// K/V rows are read once per step and never reused on chip: stream them past the caches
+__device__ __forceinline__ u32x4 ldstream(const void* p) {
+#if GKV_STREAM_NT
+  return __builtin_nontemporal_load((const u32x4*)p);
+#else
+  return *(const u32x4*)p;
+#endif
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
+// One wavefront iteration's loads: KT K tiles (A operands) and 4*KT V rows per lane.
+template <int KT>
+struct Slice {
+  u32x4 kA[KT][4];
+  u32x4 vR[4 * KT];
+};
+
+// `valid` is wave-uniform.  An invalid slice still issues its loads (all lanes read one 16-byte
+// word of row 0), so that the number of loads in flight is the same on every path and the
+// wait before consuming the previous slice can leave these outstanding.
+template <int KT>
+__device__ __forceinline__ void issue_slice(Slice<KT>& s, const char* Kh, const char* Vh, int it,
+                                            bool valid, int lane, int r, int kb) {
+  const int key0 = valid ? it * 16 * KT : 0;
+  const int lane_off = valid ? lane * 16 : 0;
+  const char* Kt = Kh + (size_t)(key0 >> 4) * TILE_BYTES + lane_off;
+#pragma unroll
+  for (int tt = 0; tt < KT; ++tt)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) s.kA[tt][c] = ldstream(Kt + (valid ? tt * TILE_BYTES + c * 1024 : 0));
+#pragma unroll
+  for (int jj = 0; jj < 4 * KT; ++jj) {
+    const int key = valid ? key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16 : 0;
+    s.vR[jj] = ldstream(Vh + (size_t)key * ROW_BYTES + (valid ? r * 16 : 0));
+  }
+}
+
+// Flash-decoding state of one wavefront: lane (head = lane%16, blk = lane/16) holds the running
+// max (in log2 units, shared by the 4 lanes of a head), its partial running sum, and
+// O[head][32*blk + 8*e + m] in oacc[m][e].
+struct Running {
+  float m_run, l_run;
+  f32x4 oacc[8];
+};
+
+// EDGE = the slice may contain the newest token's row and rows past the end: substitute k/v of
+// the newest token from the inputs, mask the rest.  The common path has none of that.
+template <int KT, bool EDGE>
+__device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const bf16x8 (&qB)[4], int it,
+                                              float scale_log2, int r, int kb, bool has_new, int len0,
+                                              int n_tot, const char* knew, const char* vnew) {
+  constexpr int NS = 4 * KT;
+  const int key0 = it * 16 * KT;
+#if GKV_EXP_NOCOMPUTE
+  {
+    u32x4 x = s.vR[0];
+#pragma unroll
+    for (int jj = 1; jj < NS; ++jj) x ^= s.vR[jj];
+#pragma unroll
+    for (int tt = 0; tt < KT; ++tt)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x ^= s.kA[tt][c];
+    st.oacc[0] += __builtin_bit_cast(f32x4, x);
+    return;
+  }
+#endif
+  if constexpr (EDGE) {
+    if (has_new && key0 <= len0) {
+      const int tt_new = (len0 - key0) >> 4, rr = len0 & 15;
+#pragma unroll
+      for (int tt = 0; tt < KT; ++tt)
+        if (tt == tt_new && r == rr) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) s.kA[tt][c] = ld16(knew + (4 * c + kb) * 16);
+        }
+#pragma unroll
+      for (int jj = 0; jj < NS; ++jj) {
+        const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
+        if (key == len0) s.vR[jj] = ld16(vnew + r * 16);
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < NS; ++jj) {
+      const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
+      if (key >= n_tot) s.vR[jj] = u32x4{0u, 0u, 0u, 0u};      // stale rows must not reach the MFMA
+    }
+  }
+
+  // scores: sc[tt][e] = q[head r] . k[key0 + 16 tt + 4 kb + e]
+  f32x4 sc[KT];
+#pragma unroll
+  for (int tt = 0; tt < KT; ++tt) {
+    sc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      sc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s.kA[tt][c]), qB[c], sc[tt], 0, 0, 0);
+  }
+  float sv[NS];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    sv[i] = sc[i >> 2][i & 3];
+    if constexpr (EDGE) {
+      const int key = key0 + (i >> 2) * 16 + 4 * kb + (i & 3);
+      if (key >= n_tot) sv[i] = -INFINITY;
+    }
+  }
+  float mx = sv[0];
+#pragma unroll
+  for (int i = 1; i < NS; ++i) mx = fmaxf(mx, sv[i]);
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(st.m_run, mx * scale_log2);       // scale > 0: max commutes with it
+  if (__any(m_new > st.m_run)) {
+    const float corr = __builtin_amdgcn_exp2f(st.m_run - m_new);
+    st.l_run *= corr;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) st.oacc[m] *= corr;
+    st.m_run = m_new;
+  }
+  float pf[NS];
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    pf[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], scale_log2, -st.m_run));
+    psum += pf[i];
+  }
+  st.l_run += psum;
+
+#if GKV_EXP_NOPV
+  {
+    u32x4 x = s.vR[0];
+#pragma unroll
+    for (int jj = 1; jj < NS; ++jj) x ^= s.vR[jj];
+    st.oacc[0] += __builtin_bit_cast(f32x4, x);
+    st.oacc[1][0] += pf[0];
+    return;
+  }
+#endif
+  // O^T[channel 8*(4 blk + e) + m, head] += V^T . P^T; the V^T operands come from an
+  // in-register transpose of the lane's [NS keys x 8 channels] block
+  if constexpr (KT == 2) {
+    f32x8 p8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p8[i] = pf[i];
+    const bf16x8 pB = __builtin_convertvector(p8, bf16x8);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      u32x4 t;
+#pragma unroll
+      for (int y = 0; y < 4; ++y)
+        t[y] = __builtin_amdgcn_perm(s.vR[2 * y + 1][m >> 1], s.vR[2 * y][m >> 1],
+                                     (m & 1) ? 0x07060302u : 0x05040100u);
+      st.oacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t), pB, st.oacc[m], 0, 0, 0);
+    }
+  } else {
+    f32x4 p4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p4[i] = pf[i];
+    const bf16x4 pB4 = __builtin_convertvector(p4, bf16x4);
+    const s16x4 pB = __builtin_bit_cast(s16x4, pB4);
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      u32x2 t;
+#pragma unroll
+      for (int y = 0; y < 2; ++y)
+        t[y] = __builtin_amdgcn_perm(s.vR[2 * y + 1][m >> 1], s.vR[2 * y][m >> 1],
+                                     (m & 1) ? 0x07060302u : 0x05040100u);
+      st.oacc[m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, t), pB, st.oacc[m], 0, 0, 0);
+    }
+  }
+}
+
+// KT = 16-key tiles per wavefront iteration (1 or 2)
+template <int NW, int KT>
+__global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
+  constexpr int KEYS = 16 * KT;             // keys per iteration
   extern __shared__ float smem[];
   __shared__ int s_misc[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -48,27 +239,15 @@ __global__ __launch_bounds__(NW * 64) void attend_mfma_kernel(GkvDims dm, Attend
   const int unit = blockIdx.x / splits, sp = blockIdx.x % splits;
   const int j = unit % dm.Hkv, lb = unit / dm.Hkv;
   const int g = dm.g, cap = dm.cap;
-
-  if (tid == 0) s_misc[0] = a.d_len[lb];
-  __syncthreads();
-  const int len0 = s_misc[0];
-  const bool has_new = (a.k_new != nullptr) && (len0 < cap);
-  if (tid == 0) {
-    // ticket: the last workgroup of this (layer, sequence) to have read the length bumps it
-    int old = atomicAdd(&a.ws.len_ticket[lb], 1);
-    if (old == dm.Hkv * splits - 1) {
-      a.ws.len_ticket[lb] = 0;
-      if (has_new) a.d_len[lb] = len0 + 1;
-    }
-  }
-  const int n_tot = len0 + (has_new ? 1 : 0);
-
   const char* Kh = (const char*)a.K + (size_t)unit * cap * ROW_BYTES;
   const char* Vh = (const char*)a.V + (size_t)unit * cap * ROW_BYTES;
-  const char* knew = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
-  const char* vnew = (const char*)a.v_new + (size_t)unit * ROW_BYTES;
+  const int stride = splits * NW;
+  int it = sp * NW + wave;
 
-  // B operand of the QK product: lane (head r, kblock kb) holds channels [8*(4c+kb), +8) of q[r]
+  // Everything whose address does not depend on the length is requested first, so that one
+  // memory latency covers it all: q (B operand of the QK product: lane (head r, kblock kb) holds
+  // channels [8*(4c+kb), +8) of q[r]), the rows this workgroup appends (split 0 only), and the
+  // first slice (its rows are inside the allocation whatever the length is).
   bf16x8 qB[4];
   {
     const char* qh = (const char*)a.q + ((size_t)lb * dm.Hq + j * g + r) * ROW_BYTES;
@@ -79,104 +258,96 @@ __global__ __launch_bounds__(NW * 64) void attend_mfma_kernel(GkvDims dm, Attend
       qB[c] = as_bf16x8(v);
     }
   }
-  const float scale_log2 = dm.scale * 1.4426950408889634f;
-
-  float m_run = -1e30f, l_run = 0.f;
-  f32x4 oacc[8];
+  const char* knew = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
+  const char* vnew = (const char*)a.v_new + (size_t)unit * ROW_BYTES;
+  // append payload, one 16-byte piece per thread and round: pieces [0,16) k_new, [16,32) v_new,
+  // [32, 32 + 16 g) the group's q rows for the window ring
+  constexpr int AP_ROUNDS = (32 + 16 * 16 + NW * 64 - 1) / (NW * 64);
+  u32x4 ap[AP_ROUNDS];
+  const bool appender = sp == 0;
+  const bool may_grow = a.k_new != nullptr;
+  if (appender) {
 #pragma unroll
-  for (int m = 0; m < 8; ++m) oacc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  const int n_iter = (n_tot + 31) >> 5;
-  for (int it = sp * NW + wave; it < n_iter; it += splits * NW) {
-    const int key0 = it << 5;
-    const char* Kt = Kh + (size_t)(key0 >> 4) * TILE_BYTES;
-    u32x4 kA[2][4];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) kA[tt][c] = ld16(Kt + tt * TILE_BYTES + c * 1024 + lane * 16);
-    u32x4 vR[8];
-#pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
-      vR[jj] = ld16(Vh + (size_t)key * ROW_BYTES + r * 16);
-    }
-    if (has_new && key0 <= len0 && len0 < key0 + 32) {       // wave-uniform
-      const int tt_new = (len0 - key0) >> 4, rr = len0 & 15;
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-        if (tt == tt_new && r == rr) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) kA[tt][c] = ld16(knew + (4 * c + kb) * 16);
-        }
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
-        if (key == len0) vR[jj] = ld16(vnew + r * 16);
+    for (int rd = 0; rd < AP_ROUNDS; ++rd) {
+      const int x = tid + rd * NW * 64;
+      if (x < 16) { if (may_grow) ap[rd] = ld16(knew + x * 16); }
+      else if (x < 32) { if (may_grow) ap[rd] = ld16(vnew + (x - 16) * 16); }
+      else if (x < 32 + 16 * g) {
+        const int h = (x - 32) >> 4, ch = (x - 32) & 15;
+        ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g + h) * ROW_BYTES + ch * 16);
       }
-    }
-    const bool tail = key0 + 32 > n_tot;                        // wave-uniform
-    if (tail) {
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
-        if (key >= n_tot) vR[jj] = u32x4{0u, 0u, 0u, 0u};    // stale rows must not reach the MFMA
-      }
-    }
-
-    // scores: sc[tt][e] = q[head r] . k[key0 + 16 tt + 4 kb + e]
-    f32x4 sc[2];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      sc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        sc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[tt][c]), qB[c], sc[tt], 0, 0, 0);
-    }
-    float s8[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      s8[i] = sc[i >> 2][i & 3] * scale_log2;
-      if (tail) {
-        const int key = key0 + (i >> 2) * 16 + 4 * kb + (i & 3);
-        if (key >= n_tot) s8[i] = -INFINITY;
-      }
-    }
-    float mx = s8[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, s8[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    if (__any(m_new > m_run)) {
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= corr;
-#pragma unroll
-      for (int m = 0; m < 8; ++m) oacc[m] *= corr;
-      m_run = m_new;
-    }
-    f32x8 p8;
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float p = __builtin_amdgcn_exp2f(s8[i] - m_run);
-      p8[i] = p;
-      psum += p;
-    }
-    l_run += psum;
-    const bf16x8 pB = __builtin_convertvector(p8, bf16x8);
-
-    // O^T[channel 8*(4 blk + e) + m, head] += V^T . P^T
-#pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      u32x4 t;
-#pragma unroll
-      for (int y = 0; y < 4; ++y)
-        t[y] = __builtin_amdgcn_perm(vR[2 * y + 1][m >> 1], vR[2 * y][m >> 1],
-                                     (m & 1) ? 0x07060302u : 0x05040100u);
-      oacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t), pB, oacc[m], 0, 0, 0);
     }
   }
+  Slice<KT> s0, s1;
+  const bool early = (it + 1) * KEYS <= cap;
+  issue_slice<KT>(s0, Kh, Vh, it, early, lane, r, kb);
+
+#if GKV_EXP_NOLEN
+  const int len0 = 576;
+  const bool has_new = true;
+  int ticket = 0;
+#else
+  if (tid == 0) s_misc[0] = a.d_len[lb];
+  __syncthreads();
+  const int len0 = s_misc[0];
+  const bool has_new = may_grow && (len0 < cap);
+  // Ticket: every workgroup of this (layer, sequence) takes one after it has read the length; the
+  // holder of the last one publishes the new length at the very end of the kernel.  The returned
+  // value is not looked at before then, so nothing waits for the atomic here.
+  int ticket = 0;
+  if (tid == 0) ticket = atomicAdd(&a.ws.len_ticket[lb], 1);
+#endif
+  const int n_tot = len0 + (has_new ? 1 : 0);
+
+  if (appender) {
+    const int slot = a.step % dm.w;
+#pragma unroll
+    for (int rd = 0; rd < AP_ROUNDS; ++rd) {
+      const int x = tid + rd * NW * 64;
+      if (x < 16) {
+        if (has_new)
+          *(u32x4*)((char*)a.K + (size_t)unit * cap * ROW_BYTES + (size_t)(len0 >> 4) * TILE_BYTES +
+                    x * 256 + (len0 & 15) * 16) = ap[rd];
+      } else if (x < 32) {
+        if (has_new)
+          *(u32x4*)((char*)a.V + (size_t)unit * cap * ROW_BYTES + (size_t)len0 * ROW_BYTES + (x - 16) * 16) = ap[rd];
+      } else if (x < 32 + 16 * g) {
+        const int h = (x - 32) >> 4, ch = (x - 32) & 15;
+        const size_t head = (size_t)lb * dm.Hq + j * g + h;
+        *(u32x4*)((char*)a.qwin + ((head * dm.w + slot) * (size_t)ROW_BYTES) + ch * 16) = ap[rd];
+      }
+    }
+    if (has_new && tid == NW * 64 - 1) a.pos[(size_t)unit * cap + len0] = a.step;
+  }
+  const float scale_log2 = dm.scale * 1.4426950408889634f;
+
+  Running st;
+  st.m_run = -1e30f;
+  st.l_run = 0.f;
+#pragma unroll
+  for (int m = 0; m < 8; ++m) st.oacc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Two slices in flight: the next slice's loads are issued before the current one is consumed.
+  const int n_iter = (n_tot + KEYS - 1) / KEYS;
+  if (!early && it < n_iter) issue_slice<KT>(s0, Kh, Vh, it, true, lane, r, kb);   // tiny capacities only
+  while (it < n_iter) {
+    const int it1 = it + stride;
+    issue_slice<KT>(s1, Kh, Vh, it1, it1 < n_iter, lane, r, kb);
+    if ((it + 1) * KEYS > len0) process_slice<KT, true>(s0, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    else process_slice<KT, false>(s0, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    if (it1 >= n_iter) break;
+    const int it2 = it1 + stride;
+    issue_slice<KT>(s0, Kh, Vh, it2, it2 < n_iter, lane, r, kb);
+    if ((it1 + 1) * KEYS > len0) process_slice<KT, true>(s1, st, qB, it1, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    else process_slice<KT, false>(s1, st, qB, it1, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    it = it2;
+  }
+  const float m_run = st.m_run, l_run = st.l_run;
+  f32x4 (&oacc)[8] = st.oacc;
+#if GKV_EXP_NOEPI
+  if (oacc[0][0] + oacc[1][0] + l_run == 123.456f) ((float*)a.out)[tid] = m_run;
+  return;
+#endif
 
   // ---- merge the wavefronts of this workgroup -------------------------------------------------
   float* so = smem;                         // [NW][g][OSTR]
@@ -257,28 +428,13 @@ __global__ __launch_bounds__(NW * 64) void attend_mfma_kernel(GkvDims dm, Attend
     }
   }
 
-  // ---- append the new row, push q into the window ring (split 0 only) -------------------------
-  if (sp == 0) {
-    if (has_new) {
-      if (tid < 16) {
-        *(u32x4*)((char*)a.K + (size_t)unit * cap * ROW_BYTES + (size_t)(len0 >> 4) * TILE_BYTES +
-                  tid * 256 + (len0 & 15) * 16) = ld16(knew + tid * 16);
-      } else if (tid < 32) {
-        const int ch = tid - 16;
-        *(u32x4*)((char*)a.V + (size_t)unit * cap * ROW_BYTES + (size_t)len0 * ROW_BYTES + ch * 16) =
-            ld16(vnew + ch * 16);
-      } else if (tid == 32) {
-        a.pos[(size_t)unit * cap + len0] = a.step;
-      }
-    }
-    const int slot = a.step % dm.w;
-    for (int x = tid; x < g * 16; x += NW * 64) {
-      const int h = x >> 4, ch = x & 15;
-      const size_t head = (size_t)lb * dm.Hq + j * g + h;
-      *(u32x4*)((char*)a.qwin + ((head * dm.w + slot) * (size_t)ROW_BYTES) + ch * 16) =
-          ld16((const char*)a.q + head * ROW_BYTES + ch * 16);
-    }
+  // ---- publish the new length (holder of the last ticket) ------------------------------------
+#if !GKV_EXP_NOLEN
+  if (tid == 0 && ticket == dm.Hkv * splits - 1) {
+    a.ws.len_ticket[lb] = 0;
+    if (has_new) a.d_len[lb] = len0 + 1;
   }
+#endif
 }
 
 }  // namespace
@@ -287,5 +443,7 @@ hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const 
   constexpr int NW = 4;
   const int units = dm.L * dm.B * dm.Hkv;
   const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 64);
-  return gkv_launch(ln, attend_mfma_kernel<NW>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
+  if (a.tile_keys == 32)
+    return gkv_launch(ln, attend_mfma_kernel<NW, 2>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
+  return gkv_launch(ln, attend_mfma_kernel<NW, 1>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
 }

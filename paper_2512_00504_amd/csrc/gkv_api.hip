@@ -80,6 +80,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   d.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : (float)(1.0 / sqrt((double)cfg->head_dim));
   c->esz = cfg->dtype == GKV_F32 ? 4 : 2;
   c->attend_splits = 0;
+  c->attend_tile = 16;
   c->force_generic = 0;
   c->mfma_ok = cfg->dtype == GKV_BF16 && d.d == 128 && d.g <= 16;
   c->prof = new (std::nothrow) GkvProfile();
@@ -191,6 +192,11 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     ctx->attend_splits = value;
     return GKV_OK;
   }
+  if (!strcmp(name, "attend_tile")) {
+    if (value != 16 && value != 32) return GKV_ERR_INVALID_ARG;
+    ctx->attend_tile = value;
+    return GKV_OK;
+  }
   if (!strcmp(name, "force_generic")) { ctx->force_generic = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
 }
@@ -216,7 +222,7 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   if (!workspace) return GKV_ERR_WORKSPACE;
   gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
   if (st != GKV_OK) return st;
-  AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_len, out, gkv_carve_workspace(ctx, workspace), 1};
+  AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_len, out, gkv_carve_workspace(ctx, workspace), 1, ctx->attend_tile};
   GkvLaunch ln{ctx, GKV_K_ATTEND, (hipStream_t)stream};
   if (use_mfma_attend(ctx)) {
     a.splits = gkv_effective_splits(ctx);

@@ -24,6 +24,7 @@ struct gkv_ctx {
   GkvDims dims;
   int32_t esz;            // bytes per element
   int32_t attend_splits;  // 0 = automatic
+  int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
   bool mfma_ok;           // bf16, d == 128, g <= 16, w % 16 == 0
   GkvProfile* prof;
@@ -55,7 +56,7 @@ struct GkvLaunch {
 struct AttendArgs {
   const void* q; const void* k_new; const void* v_new;
   void* K; void* V; int32_t* pos; int32_t step; void* qwin; int32_t* d_len; void* out;
-  GkvWorkspace ws; int32_t splits;
+  GkvWorkspace ws; int32_t splits; int32_t tile_keys;
 };
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);

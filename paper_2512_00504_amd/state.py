@@ -67,6 +67,23 @@ class DecodeState:
         kw.update(over)
         return cls(make_config(**kw), device=device, params=params)
 
+    def load_prefix(self, k, v, t0=0):
+        """Place tokens t0..t0+n-1 (k, v: [n, L, B, h_kv, d]) as cache rows 0..n-1 with positions
+        t0..t0+n-1.  For n <= budget this is exactly the state n appending decode steps leave
+        behind (nothing is evicted before the cache exceeds the budget); pure data placement."""
+        n = k.shape[0]
+        assert n <= self.cfg.budget
+        rows = torch.zeros_like(self.V)
+        rows[..., :n, :] = k.to(self.V.dtype).permute(1, 2, 3, 0, 4)
+        self.K.copy_(k_rows_to_tiled(rows))
+        rows[..., :n, :] = v.to(self.V.dtype).permute(1, 2, 3, 0, 4)
+        self.V.copy_(rows)
+        self.pos.fill_(-1)
+        self.pos[..., :n] = torch.arange(t0, t0 + n, dtype=torch.int32, device=self.device)
+        self.d_len.fill_(n)
+        self.d_n_hist.fill_(0)
+        self.len_host = n
+
     # one call each -------------------------------------------------------------------------
     def attend_decode(self, q, k_new, v_new, step):
         self.ctx.attend_decode(q, k_new, v_new, self.K, self.V, self.pos, step, self.qwin, self.d_len,
