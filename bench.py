@@ -175,7 +175,7 @@ def main():
     lib, h = st.ctx.lib, st.ctx.h
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     P = lambda t: ctypes.c_void_p(t.data_ptr())
-    pK, pV, ppos, pqwin, plen, pnh = P(st.K), P(st.V), P(st.pos), P(st.qwin), P(st.d_len), P(st.d_n_hist)
+    pK, pV, ppos, pqwin, pstate = P(st.K), P(st.V), P(st.pos), P(st.qwin), P(st.d_state)
     pout, pws, pFh, pS, pF, pkeep = P(st.out), P(st.workspace), P(st.F_hist), P(st.S), P(st.F), P(st.keep_idx)
 
     def upload(t0, n):
@@ -189,13 +189,13 @@ def main():
         len_host = st.len_host
         for i in range(n):
             t = t0 + i
-            rc = lib.gkv_attend_decode(h, qb + i * qs, kb_ + i * ks, vb + i * vs, pK, pV, ppos, t, pqwin, plen,
+            rc = lib.gkv_attend_decode(h, qb + i * qs, kb_ + i * ks, vb + i * vs, pK, pV, ppos, t, pqwin, pstate,
                                        len_host, pout, pws, stream)
             if rc:
                 raise RuntimeError(f"gkv_attend_decode failed: {rc}")
             len_host += 1
             if (t + 1) % s == 0 and len_host > b:
-                rc = lib.gkv_evict(h, pqwin, pK, pV, pFh, ppos, plen, pnh, t, len_host, pS, pF, pkeep, pws, stream)
+                rc = lib.gkv_evict(h, pqwin, pK, pV, pFh, ppos, pstate, t, len_host, pS, pF, pkeep, pws, stream)
                 if rc:
                     raise RuntimeError(f"gkv_evict failed: {rc}")
                 len_host = b
@@ -214,7 +214,8 @@ def main():
         run(qd, kd, vd, t_abs, s)
         t_abs += s
     torch.cuda.synchronize()
-    assert int(st.d_len.max()) == b and int(st.d_len.min()) == b
+    lens = st.lengths(t_abs)
+    assert int(lens.max()) == b and int(lens.min()) == b
 
     chunks = [upload(t_abs + c0, s) for c0 in range(0, K, s)]     # all timed inputs resident in HBM
     torch.cuda.synchronize()

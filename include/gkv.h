@@ -20,18 +20,32 @@
  *     gkv_workspace_init() and then left to the library.
  *   - `stream` is a hipStream_t passed as void*; calls only enqueue work on it
  *     and return.  No host synchronisation, no device-to-host copies.  Lengths
- *     live on the device (d_len, d_n_hist); `len_max_host` is only an upper
- *     bound the host knows, used to size launches and to reject overflow.
+ *     live on the device (d_state); `len_max_host` is only an upper bound the
+ *     host knows, used to size launches and to reject overflow.
+ *   - d_state is int32 [L,B,4], one record per (layer, sequence):
+ *       [GKV_ST_LEN]      cache length before decode step [GKV_ST_LEN_STEP];
+ *       [GKV_ST_LEN_STEP] the step that length refers to.  Every decode step
+ *                         appends one row, so before step t >= LEN_STEP the length
+ *                         is LEN + (t - LEN_STEP).  The decode kernel therefore never
+ *                         writes a length: no atomics, no ordering between its
+ *                         workgroups.  Compaction rewrites the pair.
+ *       [GKV_ST_N_HIST]   leading rows that carry a recorded global score.
+ *       [GKV_ST_N_TILED]  leading rows of K stored in tiled format (multiple of 16).
+ *     A fresh sequence is {prompt_len, first_step, 0, 0}.
  *   - Arrays are row-major with the last index contiguous, base pointers 16-byte
  *     aligned.  Element type of q, k_new, v_new, K, V, qwin, out is
  *     config.dtype; scores are float; lengths, positions, indices are int32.
- *   - K cache layout: each KV head's [capacity, d] block is stored in tiles of
- *     16 rows; inside a tile the 16-byte chunks are chunk-major, i.e. element
- *     (row n, channel c) sits at element offset
+ *   - K cache layout: each KV head's [capacity, d] block is a sequence of 16-row
+ *     tiles of 16*d elements.  Rows at or above N_TILED are plain row-major
+ *     (element (n, c) at n*d + c): that is how appended rows are written, one
+ *     contiguous row per step.  Rows below N_TILED are in tiled format: inside
+ *     their tile the 16-byte chunks are chunk-major, element (n, c) at
  *         (n/16)*16*d + (c/E)*16*E + (n%16)*E + c%E,   E = 16/sizeof(element),
- *     which gkv_k_offset() returns.  This makes a wavefront's matrix-core
- *     operand load of a 16-key tile one contiguous 1 KiB read.  V is plain
- *     row-major [capacity, d].
+ *     which makes a wavefront's matrix-core operand load of a 16-key tile one
+ *     contiguous 1 KiB read.  Compaction writes the kept rows in tiled format
+ *     (N_TILED = budget rounded down to 16).  A row-major K cache with
+ *     N_TILED = 0 is a valid state.  gkv_k_offset() returns the offset.
+ *     V is plain row-major [capacity, d].
  *   - Return value: GKV_OK or an error code; arguments are validated on the
  *     host before anything is enqueued, a failed call enqueues nothing.
  *     Results are deterministic: same inputs, same bits.
@@ -75,6 +89,8 @@ typedef struct gkv_config {
   float softmax_scale;              /* 0 means 1/sqrt(d) as in Eq. 1 */
 } gkv_config;
 
+enum { GKV_ST_LEN = 0, GKV_ST_LEN_STEP = 1, GKV_ST_N_HIST = 2, GKV_ST_N_TILED = 3, GKV_ST_FIELDS = 4 };
+
 typedef struct gkv_ctx gkv_ctx;     /* opaque, host memory only */
 
 /* Validates the configuration and builds a host-side context.  Touches no GPU. */
@@ -84,17 +100,19 @@ const char* gkv_status_string(gkv_status st);
 
 /* Bytes of device workspace the calls below need for this context. */
 gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes);
-/* Enqueues a fill kernel that zeroes the workspace's counters.  Call once. */
+/* Enqueues a fill kernel that zeroes the workspace's counters (used only when one
+ * unit's attention is split over several workgroups).  Call once. */
 gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream);
 
 /* Host-only helpers.
  * gkv_cache_bytes: bytes of K+V cache and of the score cache F for the whole
  * configuration at `rows` rows per KV head (paper, appendix "Memory Analysis":
  * rows = b + s for the KV cache between compressions, b - w scores per head).
- * gkv_k_offset: element offset of (row, channel) inside one KV head's K block. */
+ * gkv_k_offset: element offset of (row, channel) inside one KV head's K block when
+ * the first n_tiled rows are in tiled format. */
 gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_elem_bytes,
                            size_t* kv_bytes, size_t* score_bytes);
-int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel);
+int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_t n_tiled);
 
 /* Tuning knobs (host only): "attend_splits" (0 = automatic; set before
  * gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
@@ -104,41 +122,45 @@ gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*
  * Every decode step (paper, Preliminary: the cache the newest token attends to;
- * evicted entries are invisible to later tokens).  For every (layer, sequence)
- * with length len = d_len[l,b]:
- *   appends k_new, v_new as row len of K, V and pos[len] = step (skipped when
- *   k_new is NULL or len == capacity), stores q in slot step % w of the window
- *   ring qwin, attends q over rows [0, len] including the new one:
- *   out[i] = softmax(q[i] . K[i/g]^T * scale) V[i/g], and sets d_len = len + 1.
+ * evicted entries are invisible to later tokens).  For every (layer, sequence),
+ * with len = LEN + (step - LEN_STEP) from d_state:
+ *   attends q over rows [0, len) plus the new row (k_new, v_new):
+ *   out[i] = softmax(q[i] . K[i/g]^T * scale) V[i/g]; writes k_new, v_new as row
+ *   len of K (row-major) and V, pos[len] = step, and q into slot step % w of the
+ *   window ring qwin.  With k_new == v_new == NULL nothing is appended and the
+ *   attention covers rows [0, len) only.  d_state is not written.
  * q, out [L,B,h_q,d]; k_new, v_new [L,B,h_kv,d]; K, V [L,B,h_kv,capacity,d];
- * pos [L,B,h_kv,capacity]; qwin [L,B,h_q,w,d]; d_len [L,B].
- * len_max_host: host bound with every len <= len_max_host < capacity.
+ * pos [L,B,h_kv,capacity]; qwin [L,B,w,h_q,d] (slot-major per sequence, so one
+ * step's write is contiguous per KV group).  len_max_host: host bound with every
+ * len <= len_max_host < capacity.
  */
 gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
                              void* K, void* V, int32_t* pos, int32_t step, void* qwin,
-                             int32_t* d_len, int32_t len_max_host, void* out,
+                             const int32_t* d_state, int32_t len_max_host, void* out,
                              void* workspace, void* stream);
 
 /*
+ * The four compression calls take `step`, the index of the latest decode step;
+ * the length they see is l = LEN + (step + 1 - LEN_STEP).
+ *
  * Local score (paper, Preliminary, Eq. 1 then group max-reduce then Eq. 2).
- * With l = d_len, c = l - w: window row k is the query decoded at step
- * step - w + 1 + k (ring slot of that step), normalised over rows [0, c + k]
- * (the keys it saw when decoded); S[n] = (1/w) sum_k max_{heads of the group}
- * A[head, k, n] for the candidates n < c.  Entries n >= c are not written.
- * `step` is the step index of the latest gkv_attend_decode.  S [L,B,h_kv,capacity].
+ * With c = l - w: window row k is the query decoded at step step - w + 1 + k
+ * (its ring slot), normalised over rows [0, c + k] (the keys it saw when decoded);
+ * S[n] = (1/w) sum_k max_{heads of the group} A[head, k, n] for the candidates
+ * n < c.  Entries n >= c are not written.  S [L,B,h_kv,capacity].
  */
-gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_len,
+gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state,
                             int32_t step, int32_t len_max_host, float* S,
                             void* workspace, void* stream);
 
 /*
  * Global score (paper, Section 4).  Sn = S / max_{n<c} S per KV head;
- * F_out[n] = combine(alpha * F_hist[n], Sn[n]) for n < d_n_hist, else Sn[n].
+ * F_out[n] = combine(alpha * F_hist[n], Sn[n]) for n < N_HIST, else Sn[n].
  * combine is max, alpha*F + (1-alpha)*Sn, or alpha*F + Sn.  A zero maximum
- * gives Sn = 0.  S, F_hist, F_out [L,B,h_kv,capacity]; d_n_hist [L,B].
+ * gives Sn = 0.  S, F_hist, F_out [L,B,h_kv,capacity].
  */
 gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
-                             const int32_t* d_n_hist, const int32_t* d_len, int32_t len_max_host,
+                             const int32_t* d_state, int32_t step, int32_t len_max_host,
                              float* F_out, void* stream);
 
 /*
@@ -147,23 +169,24 @@ gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
  * index first.  keep_idx [L,B,h_kv,b-w].  Always writes valid in-range indices,
  * whatever the score bits.
  */
-gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_len,
+gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_state, int32_t step,
                            int32_t len_max_host, int32_t* keep_idx, void* workspace, void* stream);
 
 /*
  * Compaction (paper, Section 4: the kept entries' scores are recorded for the
  * next compression; appendix "Memory Analysis": cache of b rows, b-w scores).
  * In place and stable: row keep_idx[r] moves to r for r < b-w (K, V, pos),
- * F_hist[r] = F[keep_idx[r]], the w window rows [l-w, l) move to [b-w, b);
- * then d_len = b, d_n_hist = b-w.
+ * F_hist[r] = F[keep_idx[r]], the w window rows [l-w, l) move to [b-w, b).  K rows
+ * below b rounded down to 16 are written in tiled format.  Then d_state becomes
+ * {b, step + 1, b - w, b rounded down to 16}.  F must not alias F_hist.
  */
 gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
-                       float* F_hist, int32_t* pos, int32_t* d_len, int32_t* d_n_hist,
+                       float* F_hist, int32_t* pos, int32_t* d_state, int32_t step,
                        void* workspace, void* stream);
 
 /* The four compression calls above in order, on caller-provided S, F, keep_idx. */
 gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
-                     int32_t* d_len, int32_t* d_n_hist, int32_t step, int32_t len_max_host,
+                     int32_t* d_state, int32_t step, int32_t len_max_host,
                      float* S, float* F, int32_t* keep_idx, void* workspace, void* stream);
 
 /*

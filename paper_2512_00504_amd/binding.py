@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("GKV_LIB_PATH") or os.path.join(_HERE, "libgkv.so")
 
 GKV_F32, GKV_BF16 = 0, 1
 GKV_COMBINE = {"max": 0, "avg": 1, "sum": 2}
+ST_LEN, ST_LEN_STEP, ST_N_HIST, ST_N_TILED = 0, 1, 2, 3     # fields of a d_state record
 KERNEL_IDS = {"attend": 0, "score": 1, "global": 2, "topk": 3, "compact": 4}
 
 EXPORTS = [
@@ -60,14 +61,14 @@ def load_library():
     lib.gkv_workspace_bytes.argtypes = [vp, POINTER(c_size_t)]
     lib.gkv_workspace_init.argtypes = [vp, vp, vp]
     lib.gkv_cache_bytes.argtypes = [POINTER(GkvConfig), i32, i32, POINTER(c_size_t), POINTER(c_size_t)]
-    lib.gkv_k_offset.argtypes = [POINTER(GkvConfig), i32, i32]; lib.gkv_k_offset.restype = c_int64
+    lib.gkv_k_offset.argtypes = [POINTER(GkvConfig), i32, i32, i32]; lib.gkv_k_offset.restype = c_int64
     lib.gkv_set_param.argtypes = [vp, c_char_p, i32]
     lib.gkv_attend_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.gkv_score_window.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
-    lib.gkv_global_update.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
-    lib.gkv_select_topk.argtypes = [vp, vp, vp, i32, vp, vp, vp]
-    lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-    lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.gkv_global_update.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.gkv_select_topk.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.gkv_profile_enable.argtypes = [vp, i32]
     lib.gkv_profile_read.argtypes = [vp, i32, POINTER(c_double), POINTER(c_int64)]
     lib.gkv_profile_reset.argtypes = [vp]
@@ -140,31 +141,31 @@ class Context:
     def workspace_init(self, workspace):
         self._check(self.lib.gkv_workspace_init(self.h, _ptr(workspace), _stream()), "gkv_workspace_init")
 
-    def attend_decode(self, q, k_new, v_new, K, V, pos, step, qwin, d_len, len_max_host, out, workspace):
+    def attend_decode(self, q, k_new, v_new, K, V, pos, step, qwin, d_state, len_max_host, out, workspace):
         self._check(self.lib.gkv_attend_decode(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V),
-                                               _ptr(pos), step, _ptr(qwin), _ptr(d_len), len_max_host,
+                                               _ptr(pos), step, _ptr(qwin), _ptr(d_state), len_max_host,
                                                _ptr(out), _ptr(workspace), _stream()), "gkv_attend_decode")
 
-    def score_window(self, qwin, K, d_len, step, len_max_host, S, workspace):
-        self._check(self.lib.gkv_score_window(self.h, _ptr(qwin), _ptr(K), _ptr(d_len), step, len_max_host,
+    def score_window(self, qwin, K, d_state, step, len_max_host, S, workspace):
+        self._check(self.lib.gkv_score_window(self.h, _ptr(qwin), _ptr(K), _ptr(d_state), step, len_max_host,
                                               _ptr(S), _ptr(workspace), _stream()), "gkv_score_window")
 
-    def global_update(self, S, F_hist, d_n_hist, d_len, len_max_host, F_out):
-        self._check(self.lib.gkv_global_update(self.h, _ptr(S), _ptr(F_hist), _ptr(d_n_hist), _ptr(d_len),
+    def global_update(self, S, F_hist, d_state, step, len_max_host, F_out):
+        self._check(self.lib.gkv_global_update(self.h, _ptr(S), _ptr(F_hist), _ptr(d_state), step,
                                                len_max_host, _ptr(F_out), _stream()), "gkv_global_update")
 
-    def select_topk(self, F, d_len, len_max_host, keep_idx, workspace):
-        self._check(self.lib.gkv_select_topk(self.h, _ptr(F), _ptr(d_len), len_max_host, _ptr(keep_idx),
+    def select_topk(self, F, d_state, step, len_max_host, keep_idx, workspace):
+        self._check(self.lib.gkv_select_topk(self.h, _ptr(F), _ptr(d_state), step, len_max_host, _ptr(keep_idx),
                                              _ptr(workspace), _stream()), "gkv_select_topk")
 
-    def compact(self, keep_idx, F, K, V, F_hist, pos, d_len, d_n_hist, workspace):
+    def compact(self, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace):
         self._check(self.lib.gkv_compact(self.h, _ptr(keep_idx), _ptr(F), _ptr(K), _ptr(V), _ptr(F_hist),
-                                         _ptr(pos), _ptr(d_len), _ptr(d_n_hist), _ptr(workspace), _stream()),
+                                         _ptr(pos), _ptr(d_state), step, _ptr(workspace), _stream()),
                     "gkv_compact")
 
-    def evict(self, qwin, K, V, F_hist, pos, d_len, d_n_hist, step, len_max_host, S, F, keep_idx, workspace):
+    def evict(self, qwin, K, V, F_hist, pos, d_state, step, len_max_host, S, F, keep_idx, workspace):
         self._check(self.lib.gkv_evict(self.h, _ptr(qwin), _ptr(K), _ptr(V), _ptr(F_hist), _ptr(pos),
-                                       _ptr(d_len), _ptr(d_n_hist), step, len_max_host, _ptr(S), _ptr(F),
+                                       _ptr(d_state), step, len_max_host, _ptr(S), _ptr(F),
                                        _ptr(keep_idx), _ptr(workspace), _stream()), "gkv_evict")
 
     def profile_enable(self, on: bool):
@@ -196,5 +197,5 @@ def cache_bytes(cfg: GkvConfig, rows: int, score_elem_bytes: int = 4):
     return kv.value, sc.value
 
 
-def k_offset(cfg: GkvConfig, row: int, channel: int) -> int:
-    return load_library().gkv_k_offset(byref(cfg), row, channel)
+def k_offset(cfg: GkvConfig, row: int, channel: int, n_tiled: int) -> int:
+    return load_library().gkv_k_offset(byref(cfg), row, channel, n_tiled)

@@ -5,7 +5,7 @@
 
 namespace {
 
-// Dynamic LDS: float prob[cap + 1]; float qs[d]; float red[8]; int misc[2]
+// Dynamic LDS: float prob[cap + 1]; float qs[d]; float red[8]
 template <typename T>
 __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendArgs a) {
   extern __shared__ float smem[];
@@ -18,21 +18,9 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
   float* prob = smem;
   float* qs = prob + cap + 1;
   float* red = qs + d;
-  int* misc = (int*)(red + 8);
 
-  if (tid == 0) misc[0] = a.d_len[lb];
-  __syncthreads();
-  const int len0 = misc[0];
-  if (tid == 0) {
-    // Every workgroup of this (layer, sequence) has read the length once it has taken a
-    // ticket; the last one to arrive publishes the new length and re-arms the counter.
-    const bool grows = (a.k_new != nullptr) && (len0 < cap);
-    int old = atomicAdd(&a.ws.len_ticket[lb], 1);
-    if (old == dm.Hkv - 1) {
-      a.ws.len_ticket[lb] = 0;
-      if (grows) a.d_len[lb] = len0 + 1;
-    }
-  }
+  const SeqState st = load_state(a.d_state, lb);
+  const int len0 = length_before_step(st, a.step, cap);
   const bool has_new = (a.k_new != nullptr) && (len0 < cap);
   const int n_tot = len0 + (has_new ? 1 : 0);
 
@@ -54,7 +42,8 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
       if (n == len0 && has_new) {
         for (int c = 0; c < d; ++c) acc = fmaf(qs[c], Elem<T>::ld(kn + c), acc);
       } else {
-        for (int c = 0; c < d; ++c) acc = fmaf(qs[c], Elem<T>::ld(Kh + k_tiled_offset<EPC>(n, c, d)), acc);
+        for (int c = 0; c < d; ++c)
+          acc = fmaf(qs[c], Elem<T>::ld(Kh + k_elem_offset<EPC>(n, c, d, st.n_tiled)), acc);
       }
       acc *= dm.scale;
       prob[n] = acc;
@@ -68,7 +57,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
       sm += e;
     }
     sm = block_sum(sm, red);          // also makes prob[] visible to all threads
-    const float inv = 1.f / sm;
+    const float inv = sm > 0.f ? 1.f / sm : 0.f;
     T* oh = (T*)a.out + ((size_t)lb * dm.Hq + head) * d;
     for (int c = tid; c < d; c += blockDim.x) {
       float acc = 0.f;
@@ -78,22 +67,22 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
     }
   }
 
-  // Append the new row and push q into the window ring, after all reads of this unit's cache.
+  // Append the new row (row-major: len0 >= n_tiled always) and push q into the window ring,
+  // after all reads of this unit's cache.
   __syncthreads();
   if (has_new) {
     T* Kw = (T*)a.K + (size_t)unit * cap * d;
     T* Vw = (T*)a.V + (size_t)unit * cap * d;
     for (int c = tid; c < d; c += blockDim.x) {
-      Kw[k_tiled_offset<EPC>(len0, c, d)] = kn[c];
+      Kw[(size_t)len0 * d + c] = kn[c];
       Vw[(size_t)len0 * d + c] = vn[c];
     }
     if (tid == 0) a.pos[(size_t)unit * cap + len0] = a.step;
   }
   const int slot = a.step % dm.w;
   for (int x = tid; x < g * d; x += blockDim.x) {
-    const int hi = x / d, c = x % d;
-    const int head = j * g + hi;
-    ((T*)a.qwin)[(((size_t)lb * dm.Hq + head) * dm.w + slot) * d + c] =
+    const int head = j * g + x / d, c = x % d;
+    ((T*)a.qwin)[(((size_t)lb * dm.w + slot) * dm.Hq + head) * d + c] =
         ((const T*)a.q)[((size_t)lb * dm.Hq + head) * d + c];
   }
 }
@@ -102,7 +91,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
 
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a) {
   const int units = dm.L * dm.B * dm.Hkv;
-  const size_t shmem = sizeof(float) * (dm.cap + 1 + dm.d + 8) + 2 * sizeof(int);
+  const size_t shmem = sizeof(float) * (dm.cap + 1 + dm.d + 8);
   if (dtype == GKV_F32)
     return gkv_launch(ln, attend_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);
   return gkv_launch(ln, attend_generic_kernel<uint16_t>, dim3(units), dim3(256), shmem, dm, a);

@@ -1,18 +1,19 @@
 // Decode attention on the matrix cores: bf16, head_dim 128, group size g <= 16.
 //
-// One workgroup of NW wavefronts per (unit, split).  A wavefront owns 32-key slices of the
-// cache (slice it, it + splits*NW, ...) and keeps flash-decoding state (running max, running
-// sum, fp32 accumulators) for all g query heads of the KV group, so K and V are read from
-// HBM exactly once per KV head.
+// One workgroup of NW wavefronts per (unit, split).  A wavefront owns slices of 16 (or 32) keys
+// of the cache (slice it, it + splits*NW, ...) and keeps flash-decoding state (running max,
+// running sum, fp32 accumulators) for all g query heads of the KV group, so K and V are read
+// from HBM exactly once per KV head.
 //
-// Per 32-key slice and wavefront:
-//   K: two 16-key tiles.  The tiled K layout makes each matrix-core A operand
-//      (16 keys x 32 channels, lane = key + 16*kblock) one contiguous 1 KiB load.
+// Per slice and wavefront:
+//   K: 16-key tiles.  In the tiled K format each matrix-core A operand (16 keys x 32 channels,
+//      lane = key + 16*kblock) is one contiguous 1 KiB load; the few tiles appended since the
+//      last compaction are row-major and load as 16 rows x 64 bytes.
 //      S^T[key, head] = K[key, :] . Q[head, :]  -> 4 MFMA 16x16x32 per tile.
-//      The result lane (head = lane%16, blk = lane/16) holds 8 keys of its head.
+//      The result lane (head = lane%16, blk = lane/16) holds 4 keys of its head per tile.
 //   softmax: running max shared by the 4 lanes of a head (2 cross-lane exchanges), exp2.
-//   V: lane (chunk = lane%16, kb = lane/16) loads the 16-byte chunk `chunk` of 8 keys, so a
-//      quarter-wave reads one full 256-byte row per load.  An 8x8 in-register transpose
+//   V: lane (chunk = lane%16, kb = lane/16) loads the 16-byte chunk `chunk` of 4 keys per tile,
+//      so a quarter-wave reads one full 256-byte row per load.  An in-register transpose
 //      (v_perm_b32) turns that into A operands V^T[channel, key]; with B = P^T[key, head]
 //      (the probabilities, already in the right lanes) 8 MFMAs give O^T[channel, head].
 // The wavefronts of a workgroup are merged through LDS; splits of one unit are merged by the
@@ -20,22 +21,13 @@
 //
 // The newest token's k/v are not read from the cache (another workgroup may be writing that
 // row): the lanes that would hold row `len` take them from k_new / v_new instead.
+// All stores (output, the appended K/V rows, the window-ring slot) are issued at the end of
+// the workgroup and are whole contiguous rows: stores mixed into the read stream, partial-line
+// stores and atomics each cost several microseconds per launch on this memory system.
 #include "gkv_internal.h"
 
 #ifndef GKV_STREAM_NT
 #define GKV_STREAM_NT 1
-#endif
-#ifndef GKV_EXP_NOCOMPUTE
-#define GKV_EXP_NOCOMPUTE 0      // experiment: skip the arithmetic, keep the loads
-#endif
-#ifndef GKV_EXP_NOEPI
-#define GKV_EXP_NOEPI 0          // experiment: skip merge, output and append
-#endif
-#ifndef GKV_EXP_NOLEN
-#define GKV_EXP_NOLEN 0          // experiment: do not read the length or take the ticket
-#endif
-#ifndef GKV_EXP_NOPV
-#define GKV_EXP_NOPV 0           // experiment: skip the P.V product
 #endif
 
 namespace {
@@ -72,23 +64,27 @@ struct Slice {
   u32x4 vR[4 * KT];
 };
 
-// `valid` is wave-uniform.  An invalid slice still issues its loads (all lanes read one 16-byte
-// word of row 0), so that the number of loads in flight is the same on every path and the
-// wait before consuming the previous slice can leave these outstanding.
+// Tiles below n_tiled are in tiled format (lane-contiguous 1 KiB per load); tiles above are
+// row-major, where the same operand is 16 rows x 64 bytes per load (only the rows appended since
+// the last compaction are in that state).
 template <int KT>
 __device__ __forceinline__ void issue_slice(Slice<KT>& s, const char* Kh, const char* Vh, int it,
-                                            bool valid, int lane, int r, int kb) {
-  const int key0 = valid ? it * 16 * KT : 0;
-  const int lane_off = valid ? lane * 16 : 0;
-  const char* Kt = Kh + (size_t)(key0 >> 4) * TILE_BYTES + lane_off;
+                                            int n_tiled, int lane, int r, int kb) {
+  const int key0 = it * 16 * KT;
 #pragma unroll
-  for (int tt = 0; tt < KT; ++tt)
+  for (int tt = 0; tt < KT; ++tt) {
+    const int row0 = key0 + 16 * tt;
+    const char* Kt = Kh + (size_t)(row0 >> 4) * TILE_BYTES;
+    const bool tiled = row0 < n_tiled;                     // wave-uniform
+    const int lane_off = tiled ? lane * 16 : r * ROW_BYTES + kb * 16;
+    const int step_off = tiled ? 1024 : 64;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) s.kA[tt][c] = ldstream(Kt + (valid ? tt * TILE_BYTES + c * 1024 : 0));
+    for (int c = 0; c < 4; ++c) s.kA[tt][c] = ldstream(Kt + lane_off + c * step_off);
+  }
 #pragma unroll
   for (int jj = 0; jj < 4 * KT; ++jj) {
-    const int key = valid ? key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16 : 0;
-    s.vR[jj] = ldstream(Vh + (size_t)key * ROW_BYTES + (valid ? r * 16 : 0));
+    const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
+    s.vR[jj] = ldstream(Vh + (size_t)key * ROW_BYTES + r * 16);
   }
 }
 
@@ -108,19 +104,6 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
                                               int n_tot, const char* knew, const char* vnew) {
   constexpr int NS = 4 * KT;
   const int key0 = it * 16 * KT;
-#if GKV_EXP_NOCOMPUTE
-  {
-    u32x4 x = s.vR[0];
-#pragma unroll
-    for (int jj = 1; jj < NS; ++jj) x ^= s.vR[jj];
-#pragma unroll
-    for (int tt = 0; tt < KT; ++tt)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) x ^= s.kA[tt][c];
-    st.oacc[0] += __builtin_bit_cast(f32x4, x);
-    return;
-  }
-#endif
   if constexpr (EDGE) {
     if (has_new && key0 <= len0) {
       const int tt_new = (len0 - key0) >> 4, rr = len0 & 15;
@@ -183,16 +166,6 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
   }
   st.l_run += psum;
 
-#if GKV_EXP_NOPV
-  {
-    u32x4 x = s.vR[0];
-#pragma unroll
-    for (int jj = 1; jj < NS; ++jj) x ^= s.vR[jj];
-    st.oacc[0] += __builtin_bit_cast(f32x4, x);
-    st.oacc[1][0] += pf[0];
-    return;
-  }
-#endif
   // O^T[channel 8*(4 blk + e) + m, head] += V^T . P^T; the V^T operands come from an
   // in-register transpose of the lane's [NS keys x 8 channels] block
   if constexpr (KT == 2) {
@@ -229,7 +202,7 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
 
 // KT = 16-key tiles per wavefront iteration (1 or 2)
 template <int NW, int KT>
-__global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
+__global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
   constexpr int KEYS = 16 * KT;             // keys per iteration
   extern __shared__ float smem[];
   __shared__ int s_misc[2];
@@ -242,12 +215,15 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(G
   const char* Kh = (const char*)a.K + (size_t)unit * cap * ROW_BYTES;
   const char* Vh = (const char*)a.V + (size_t)unit * cap * ROW_BYTES;
   const int stride = splits * NW;
-  int it = sp * NW + wave;
 
-  // Everything whose address does not depend on the length is requested first, so that one
-  // memory latency covers it all: q (B operand of the QK product: lane (head r, kblock kb) holds
-  // channels [8*(4c+kb), +8) of q[r]), the rows this workgroup appends (split 0 only), and the
-  // first slice (its rows are inside the allocation whatever the length is).
+  // The length comes from the state record and the step number; nothing is written back, so
+  // the workgroups of a (layer, sequence) need no ordering among themselves.
+  const SeqState seq = load_state(a.d_state, lb);
+  const int len0 = length_before_step(seq, a.step, cap);
+  const bool has_new = (a.k_new != nullptr) && (len0 < cap);
+  const int n_tot = len0 + (has_new ? 1 : 0);
+
+  // B operand of the QK product: lane (head r, kblock kb) holds channels [8*(4c+kb), +8) of q[r]
   bf16x8 qB[4];
   {
     const char* qh = (const char*)a.q + ((size_t)lb * dm.Hq + j * g + r) * ROW_BYTES;
@@ -260,64 +236,20 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(G
   }
   const char* knew = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
   const char* vnew = (const char*)a.v_new + (size_t)unit * ROW_BYTES;
-  // append payload, one 16-byte piece per thread and round: pieces [0,16) k_new, [16,32) v_new,
-  // [32, 32 + 16 g) the group's q rows for the window ring
+  // What this workgroup stores at the end besides the output (split 0 only), one 16-byte piece
+  // per thread and round: pieces [0,16) k_new, [16,32) v_new, [32, 32 + 16 g) the group's q rows
+  // for the window ring.  Requested now so that the latency is long gone by then.
   constexpr int AP_ROUNDS = (32 + 16 * 16 + NW * 64 - 1) / (NW * 64);
   u32x4 ap[AP_ROUNDS];
   const bool appender = sp == 0;
-  const bool may_grow = a.k_new != nullptr;
   if (appender) {
 #pragma unroll
     for (int rd = 0; rd < AP_ROUNDS; ++rd) {
       const int x = tid + rd * NW * 64;
-      if (x < 16) { if (may_grow) ap[rd] = ld16(knew + x * 16); }
-      else if (x < 32) { if (may_grow) ap[rd] = ld16(vnew + (x - 16) * 16); }
-      else if (x < 32 + 16 * g) {
-        const int h = (x - 32) >> 4, ch = (x - 32) & 15;
-        ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g + h) * ROW_BYTES + ch * 16);
-      }
+      if (x < 16) { if (has_new) ap[rd] = ld16(knew + x * 16); }
+      else if (x < 32) { if (has_new) ap[rd] = ld16(vnew + (x - 16) * 16); }
+      else if (x < 32 + 16 * g) ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16);
     }
-  }
-  Slice<KT> s0, s1;
-  const bool early = (it + 1) * KEYS <= cap;
-  issue_slice<KT>(s0, Kh, Vh, it, early, lane, r, kb);
-
-#if GKV_EXP_NOLEN
-  const int len0 = 576;
-  const bool has_new = true;
-  int ticket = 0;
-#else
-  if (tid == 0) s_misc[0] = a.d_len[lb];
-  __syncthreads();
-  const int len0 = s_misc[0];
-  const bool has_new = may_grow && (len0 < cap);
-  // Ticket: every workgroup of this (layer, sequence) takes one after it has read the length; the
-  // holder of the last one publishes the new length at the very end of the kernel.  The returned
-  // value is not looked at before then, so nothing waits for the atomic here.
-  int ticket = 0;
-  if (tid == 0) ticket = atomicAdd(&a.ws.len_ticket[lb], 1);
-#endif
-  const int n_tot = len0 + (has_new ? 1 : 0);
-
-  if (appender) {
-    const int slot = a.step % dm.w;
-#pragma unroll
-    for (int rd = 0; rd < AP_ROUNDS; ++rd) {
-      const int x = tid + rd * NW * 64;
-      if (x < 16) {
-        if (has_new)
-          *(u32x4*)((char*)a.K + (size_t)unit * cap * ROW_BYTES + (size_t)(len0 >> 4) * TILE_BYTES +
-                    x * 256 + (len0 & 15) * 16) = ap[rd];
-      } else if (x < 32) {
-        if (has_new)
-          *(u32x4*)((char*)a.V + (size_t)unit * cap * ROW_BYTES + (size_t)len0 * ROW_BYTES + (x - 16) * 16) = ap[rd];
-      } else if (x < 32 + 16 * g) {
-        const int h = (x - 32) >> 4, ch = (x - 32) & 15;
-        const size_t head = (size_t)lb * dm.Hq + j * g + h;
-        *(u32x4*)((char*)a.qwin + ((head * dm.w + slot) * (size_t)ROW_BYTES) + ch * 16) = ap[rd];
-      }
-    }
-    if (has_new && tid == NW * 64 - 1) a.pos[(size_t)unit * cap + len0] = a.step;
   }
   const float scale_log2 = dm.scale * 1.4426950408889634f;
 
@@ -327,27 +259,15 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(G
 #pragma unroll
   for (int m = 0; m < 8; ++m) st.oacc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Two slices in flight: the next slice's loads are issued before the current one is consumed.
   const int n_iter = (n_tot + KEYS - 1) / KEYS;
-  if (!early && it < n_iter) issue_slice<KT>(s0, Kh, Vh, it, true, lane, r, kb);   // tiny capacities only
-  while (it < n_iter) {
-    const int it1 = it + stride;
-    issue_slice<KT>(s1, Kh, Vh, it1, it1 < n_iter, lane, r, kb);
-    if ((it + 1) * KEYS > len0) process_slice<KT, true>(s0, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
-    else process_slice<KT, false>(s0, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
-    if (it1 >= n_iter) break;
-    const int it2 = it1 + stride;
-    issue_slice<KT>(s0, Kh, Vh, it2, it2 < n_iter, lane, r, kb);
-    if ((it1 + 1) * KEYS > len0) process_slice<KT, true>(s1, st, qB, it1, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
-    else process_slice<KT, false>(s1, st, qB, it1, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
-    it = it2;
+  for (int it = sp * NW + wave; it < n_iter; it += stride) {
+    Slice<KT> s;
+    issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
+    if ((it + 1) * KEYS > len0) process_slice<KT, true>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    else process_slice<KT, false>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
   }
   const float m_run = st.m_run, l_run = st.l_run;
   f32x4 (&oacc)[8] = st.oacc;
-#if GKV_EXP_NOEPI
-  if (oacc[0][0] + oacc[1][0] + l_run == 123.456f) ((float*)a.out)[tid] = m_run;
-  return;
-#endif
 
   // ---- merge the wavefronts of this workgroup -------------------------------------------------
   float* so = smem;                         // [NW][g][OSTR]
@@ -395,6 +315,25 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(G
     }
   }
 
+  // ---- append the new row (row-major, one contiguous row each for K and V), push q into the
+  //      window ring (contiguous per KV group).  Rows the other workgroups may still be reading
+  //      are never the new row's source: they take k_new / v_new from the inputs. ---------------
+  if (appender) {
+    const int slot = a.step % dm.w;
+#pragma unroll
+    for (int rd = 0; rd < AP_ROUNDS; ++rd) {
+      const int x = tid + rd * NW * 64;
+      if (x < 16) {
+        if (has_new) *(u32x4*)((char*)a.K + ((size_t)unit * cap + len0) * ROW_BYTES + x * 16) = ap[rd];
+      } else if (x < 32) {
+        if (has_new) *(u32x4*)((char*)a.V + ((size_t)unit * cap + len0) * ROW_BYTES + (x - 16) * 16) = ap[rd];
+      } else if (x < 32 + 16 * g) {
+        *(u32x4*)((char*)a.qwin + (((size_t)lb * dm.w + slot) * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16) = ap[rd];
+      }
+    }
+    if (has_new && tid == NW * 64 - 1) a.pos[(size_t)unit * cap + len0] = a.step;
+  }
+
   // ---- merge the splits of this unit: last workgroup to finish does it ------------------------
   if (splits > 1) {
     __threadfence();
@@ -427,14 +366,6 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 3 : 2) void attend_mfma_kernel(G
       }
     }
   }
-
-  // ---- publish the new length (holder of the last ticket) ------------------------------------
-#if !GKV_EXP_NOLEN
-  if (tid == 0 && ticket == dm.Hkv * splits - 1) {
-    a.ws.len_ticket[lb] = 0;
-    if (has_new) a.d_len[lb] = len0 + 1;
-  }
-#endif
 }
 
 }  // namespace

@@ -31,15 +31,15 @@ __device__ __forceinline__ uint32_t sortable_key(float f) {
 // ---- global score (Section 4) --------------------------------------------------------------
 __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const float* __restrict__ S,
                                                             const float* __restrict__ F_hist,
-                                                            const int32_t* __restrict__ d_n_hist,
-                                                            const int32_t* __restrict__ d_len,
+                                                            const int32_t* __restrict__ d_state, int step,
                                                             float* __restrict__ F_out) {
   __shared__ float red[8];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  const int l = d_len[lb];
-  if (l <= dm.b || l > dm.cap) return;
+  const SeqState st = load_state(d_state, lb);
+  const int l = length_before_step(st, step + 1, dm.cap);
+  if (l <= dm.b) return;
   const int c = l - dm.w;
-  int n_hist = d_n_hist[lb];
+  int n_hist = st.n_hist;
   n_hist = n_hist < 0 ? 0 : (n_hist > c ? c : n_hist);
   const float* Su = S + (size_t)unit * dm.cap;
   const float* Hu = F_hist + (size_t)unit * dm.cap;
@@ -63,15 +63,15 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
 // ---- top-(b-w): exact radix select on the float bits, ties to the lower index ---------------
 // Dynamic LDS: uint32 keys[cap]
 __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const float* __restrict__ F,
-                                                          const int32_t* __restrict__ d_len,
+                                                          const int32_t* __restrict__ d_state, int step,
                                                           int32_t* __restrict__ keep_idx) {
   extern __shared__ uint32_t keys[];
   __shared__ int hist[256];
   __shared__ int tmp[4];
   __shared__ int sel[2];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  const int l = d_len[lb];
-  if (l <= dm.b || l > dm.cap) return;
+  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
+  if (l <= dm.b) return;
   const int c = l - dm.w;
   const int k = dm.b - dm.w;                   // c > k because l > b
   const float* Fu = F + (size_t)unit * dm.cap;
@@ -124,24 +124,30 @@ __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const floa
 }
 
 // ---- compaction ----------------------------------------------------------------------------
-// grid (units, 2): y = 0 moves K (tiled layout), pos and F_hist; y = 1 moves V (row-major).
-// Rows are produced in ascending chunks: load every source piece of the chunk, barrier, store.
-// Destination index <= source index and sources ascend, so a chunk's stores never touch a
-// source that a later chunk still has to read.
+// grid (units, 2): y = 0 moves K, pos and F_hist; y = 1 moves V (row-major).
+// K source rows are in tiled format below the old N_TILED and row-major above; destination rows
+// are tiled below nt_new = b rounded down to 16 and row-major above.  Both formats keep a
+// 16-row tile inside the same tile-sized block, so the stable-compaction argument still holds
+// with chunks that start on tile boundaries: rows are produced in ascending chunks, every
+// source piece of a chunk is loaded, then a barrier, then the stores.  Destination index <=
+// source index and sources ascend, so a chunk's stores (which stay inside the chunk's tiles)
+// never touch a row that a later chunk still has to read.
 template <int PPT>
 __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const int32_t* __restrict__ keep_idx,
                                                       const float* __restrict__ F, void* K, void* V,
                                                       float* __restrict__ F_hist, int32_t* pos,
-                                                      const int32_t* __restrict__ d_len) {
+                                                      const int32_t* __restrict__ d_state, int step) {
   __shared__ int red_i[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const bool isK = blockIdx.y == 0;
-  const int l = d_len[lb];
-  if (l <= dm.b || l > dm.cap) return;
+  const SeqState st = load_state(d_state, lb);
+  const int l = length_before_step(st, step + 1, dm.cap);
+  if (l <= dm.b) return;
   const int c = l - dm.w, k = dm.b - dm.w, b = dm.b;
+  const int nt_old = st.n_tiled, nt_new = b & ~15;
   const int32_t* Ku = keep_idx + (size_t)unit * k;
 
-  // first destination row whose source differs from it
+  // first destination row whose source differs from it; a K format change rewrites everything
   int first = k;
   for (int n = tid; n < k; n += 256)
     if (Ku[n] != n) { first = n; break; }        // ascending per thread: the first hit is its minimum
@@ -149,6 +155,8 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   if ((tid & 63) == 0) red_i[tid >> 6] = first;
   __syncthreads();
   first = min(min(red_i[0], red_i[1]), min(red_i[2], red_i[3]));
+  if (isK && nt_old != nt_new) first = 0;
+  first &= ~15;                                  // chunks start on tile boundaries
 
   if (isK) {
     float* Hu = F_hist + (size_t)unit * dm.cap;
@@ -161,7 +169,8 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   }
 
   const int NP = dm.d * esz / 16;                // 16-byte pieces per row
-  const int R = (256 * PPT) / NP;                // rows per chunk
+  int R = (256 * PPT) / NP;                      // rows per chunk: whole tiles, at most one per thread
+  R = (R > 256 ? 256 : R) & ~15;
   uint4* base = (uint4*)((char*)(isK ? K : V) + (size_t)unit * dm.cap * dm.d * esz);
   int32_t* pu = pos + (size_t)unit * dm.cap;
 
@@ -178,8 +187,8 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
       if (rr < R && row < b) {
         int src = row < k ? Ku[row] : c + (row - k);
         src = src < 0 ? 0 : (src >= l ? l - 1 : src);
-        const int so = isK ? ((src >> 4) * 16 * NP + piece * 16 + (src & 15)) : (src * NP + piece);
-        dst[i] = isK ? ((row >> 4) * 16 * NP + piece * 16 + (row & 15)) : (row * NP + piece);
+        const int so = (isK && src < nt_old) ? ((src >> 4) * 16 * NP + piece * 16 + (src & 15)) : (src * NP + piece);
+        dst[i] = (isK && row < nt_new) ? ((row >> 4) * 16 * NP + piece * 16 + (row & 15)) : (row * NP + piece);
         buf[i] = base[so];
       }
     }
@@ -198,14 +207,12 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   }
 }
 
-__global__ void finalize_lengths_kernel(GkvDims dm, int32_t* d_len, int32_t* d_n_hist) {
+__global__ void finalize_state_kernel(GkvDims dm, int32_t* d_state, int step) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= dm.L * dm.B) return;
-  const int l = d_len[i];
-  if (l > dm.b && l <= dm.cap) {
-    d_len[i] = dm.b;
-    d_n_hist[i] = dm.b - dm.w;
-  }
+  const SeqState st = load_state(d_state, i);
+  const int l = length_before_step(st, step + 1, dm.cap);
+  if (l > dm.b) *(int4*)(d_state + 4 * (size_t)i) = make_int4(dm.b, step + 1, dm.b - dm.w, dm.b & ~15);
 }
 
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {
@@ -216,28 +223,28 @@ __global__ void fill_zero_kernel(int32_t* p, size_t n) {
 }  // namespace
 
 hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
-                                    const float* F_hist, const int32_t* d_n_hist,
-                                    const int32_t* d_len, float* F_out) {
+                                    const float* F_hist, const int32_t* d_state, int32_t step, float* F_out) {
   const int units = dm.L * dm.B * dm.Hkv;
-  return gkv_launch(ln, global_update_kernel, dim3(units), dim3(256), 0, dm, S, F_hist, d_n_hist, d_len, F_out);
+  return gkv_launch(ln, global_update_kernel, dim3(units), dim3(256), 0, dm, S, F_hist, d_state, (int)step, F_out);
 }
 
 hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
-                                  const int32_t* d_len, int32_t* keep_idx) {
+                                  const int32_t* d_state, int32_t step, int32_t* keep_idx) {
   const int units = dm.L * dm.B * dm.Hkv;
-  return gkv_launch(ln, select_topk_kernel, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, F, d_len, keep_idx);
+  return gkv_launch(ln, select_topk_kernel, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, F, d_state,
+                    (int)step, keep_idx);
 }
 
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
-                              int32_t* d_len, int32_t* d_n_hist) {
+                              int32_t* d_state, int32_t step) {
   const int units = dm.L * dm.B * dm.Hkv;
   hipError_t e = gkv_launch(ln, compact_kernel<4>, dim3(units, 2), dim3(256), 0, dm, esz, keep_idx, F, K, V,
-                            F_hist, pos, (const int32_t*)d_len);
+                            F_hist, pos, (const int32_t*)d_state, (int)step);
   if (e != hipSuccess) return e;
   const int nlb = dm.L * dm.B;
   GkvLaunch plain{ln.ctx, -1, ln.stream};
-  return gkv_launch(plain, finalize_lengths_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_len, d_n_hist);
+  return gkv_launch(plain, finalize_state_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_state, (int)step);
 }
 
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n) {

@@ -7,8 +7,6 @@
 
 #include "gkv_internal.h"
 
-bool gkv_score_mfma_supported(int g, int w);
-
 // ---- profiling ----------------------------------------------------------------------------------
 struct GkvProfile {
   bool on = false;
@@ -56,7 +54,7 @@ static gkv_status validate_config(const gkv_config* c) {
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return GKV_ERR_INVALID_ARG;
   const int esz = c->dtype == GKV_F32 ? 4 : 2;
   const int epc = 16 / esz;
-  if (c->head_dim % epc != 0 || c->head_dim > 1024) return GKV_ERR_SHAPE;
+  if (c->head_dim % epc != 0 || c->head_dim * esz > 1024) return GKV_ERR_SHAPE;
   if (c->capacity < c->budget + c->interval || c->capacity % 32 != 0 || c->capacity > 4096)
     return GKV_ERR_SHAPE;
   const int64_t units = (int64_t)c->n_layers * c->batch * c->n_kv_heads;
@@ -139,9 +137,7 @@ static size_t ws_partials_bytes(const gkv_ctx* ctx) {
 GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
   GkvWorkspace w;
   char* p = (char*)base;
-  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
-  const size_t units = nlb * ctx->dims.Hkv;
-  w.len_ticket = (int32_t*)p; p += gkv_align256(nlb * 4);
+  const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
   w.split_ticket = (int32_t*)p; p += gkv_align256(units * 4);
   w.partials = (float*)p;
   return w;
@@ -149,18 +145,16 @@ GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
 
 extern "C" gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes) {
   if (!ctx || !out_bytes) return GKV_ERR_INVALID_ARG;
-  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
-  const size_t units = nlb * ctx->dims.Hkv;
-  *out_bytes = gkv_align256(nlb * 4) + gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx)) + 256;
+  const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
+  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx)) + 256;
   return GKV_OK;
 }
 
 extern "C" gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream) {
   if (!ctx) return GKV_ERR_INVALID_ARG;
   if (!workspace) return GKV_ERR_WORKSPACE;
-  const size_t nlb = (size_t)ctx->dims.L * ctx->dims.B;
-  const size_t units = nlb * ctx->dims.Hkv;
-  const size_t n = (gkv_align256(nlb * 4) + gkv_align256(units * 4)) / 4;
+  const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
+  const size_t n = gkv_align256(units * 4) / 4;
   return gkv_launch_fill_zero((hipStream_t)stream, (int32_t*)workspace, n) == hipSuccess ? GKV_OK : GKV_ERR_HIP;
 }
 
@@ -178,10 +172,11 @@ extern "C" gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32
   return GKV_OK;
 }
 
-extern "C" int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel) {
-  if (!cfg || row < 0 || channel < 0 || channel >= cfg->head_dim) return -1;
+extern "C" int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_t n_tiled) {
+  if (!cfg || row < 0 || channel < 0 || channel >= cfg->head_dim || n_tiled < 0) return -1;
   const int epc = cfg->dtype == GKV_F32 ? 4 : 8;
   const int64_t d = cfg->head_dim;
+  if (row >= (n_tiled & ~15)) return (int64_t)row * d + channel;
   return (int64_t)(row / 16) * 16 * d + (int64_t)(channel / epc) * (16 * epc) + (row % 16) * epc + channel % epc;
 }
 
@@ -215,14 +210,15 @@ static inline gkv_status hip_status(hipError_t e) { return e == hipSuccess ? GKV
 
 extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
                                         void* K, void* V, int32_t* pos, int32_t step, void* qwin,
-                                        int32_t* d_len, int32_t len_max_host, void* out,
+                                        const int32_t* d_state, int32_t len_max_host, void* out,
                                         void* workspace, void* stream) {
-  if (!ctx || !q || !K || !V || !pos || !qwin || !d_len || !out || step < 0) return GKV_ERR_INVALID_ARG;
+  if (!ctx || !q || !K || !V || !pos || !qwin || !d_state || !out || step < 0) return GKV_ERR_INVALID_ARG;
   if ((k_new == nullptr) != (v_new == nullptr)) return GKV_ERR_INVALID_ARG;
   if (!workspace) return GKV_ERR_WORKSPACE;
   gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
   if (st != GKV_OK) return st;
-  AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_len, out, gkv_carve_workspace(ctx, workspace), 1, ctx->attend_tile};
+  AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_state, out, gkv_carve_workspace(ctx, workspace), 1,
+               ctx->attend_tile};
   GkvLaunch ln{ctx, GKV_K_ATTEND, (hipStream_t)stream};
   if (use_mfma_attend(ctx)) {
     a.splits = gkv_effective_splits(ctx);
@@ -231,64 +227,64 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   return hip_status(gkv_launch_attend_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 
-extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_len,
+extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state,
                                        int32_t step, int32_t len_max_host, float* S,
                                        void* workspace, void* stream) {
   (void)workspace;
-  if (!ctx || !qwin || !K || !d_len || !S || step < 0) return GKV_ERR_INVALID_ARG;
+  if (!ctx || !qwin || !K || !d_state || !S || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  ScoreArgs a{qwin, K, d_len, step, S};
+  ScoreArgs a{qwin, K, d_state, step, S};
   GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
   if (use_mfma_score(ctx)) return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
   return hip_status(gkv_launch_score_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 
 extern "C" gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
-                                        const int32_t* d_n_hist, const int32_t* d_len,
-                                        int32_t len_max_host, float* F_out, void* stream) {
-  if (!ctx || !S || !F_hist || !d_n_hist || !d_len || !F_out) return GKV_ERR_INVALID_ARG;
+                                        const int32_t* d_state, int32_t step, int32_t len_max_host,
+                                        float* F_out, void* stream) {
+  if (!ctx || !S || !F_hist || !d_state || !F_out || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
   GkvLaunch ln{ctx, GKV_K_GLOBAL, (hipStream_t)stream};
-  return hip_status(gkv_launch_global_update(ln, ctx->dims, S, F_hist, d_n_hist, d_len, F_out));
+  return hip_status(gkv_launch_global_update(ln, ctx->dims, S, F_hist, d_state, step, F_out));
 }
 
-extern "C" gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_len,
+extern "C" gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_state, int32_t step,
                                       int32_t len_max_host, int32_t* keep_idx, void* workspace, void* stream) {
   (void)workspace;
-  if (!ctx || !F || !d_len || !keep_idx) return GKV_ERR_INVALID_ARG;
+  if (!ctx || !F || !d_state || !keep_idx || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
   GkvLaunch ln{ctx, GKV_K_TOPK, (hipStream_t)stream};
-  return hip_status(gkv_launch_select_topk(ln, ctx->dims, F, d_len, keep_idx));
+  return hip_status(gkv_launch_select_topk(ln, ctx->dims, F, d_state, step, keep_idx));
 }
 
 extern "C" gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
-                                  float* F_hist, int32_t* pos, int32_t* d_len, int32_t* d_n_hist,
+                                  float* F_hist, int32_t* pos, int32_t* d_state, int32_t step,
                                   void* workspace, void* stream) {
   (void)workspace;
-  if (!ctx || !keep_idx || !F || !K || !V || !F_hist || !pos || !d_len || !d_n_hist) return GKV_ERR_INVALID_ARG;
+  if (!ctx || !keep_idx || !F || !K || !V || !F_hist || !pos || !d_state || step < 0) return GKV_ERR_INVALID_ARG;
   if (F == F_hist) return GKV_ERR_INVALID_ARG;
   GkvLaunch ln{ctx, GKV_K_COMPACT, (hipStream_t)stream};
-  return hip_status(gkv_launch_compact(ln, ctx->dims, ctx->esz, keep_idx, F, K, V, F_hist, pos, d_len, d_n_hist));
+  return hip_status(gkv_launch_compact(ln, ctx->dims, ctx->esz, keep_idx, F, K, V, F_hist, pos, d_state, step));
 }
 
 extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
-                                int32_t* d_len, int32_t* d_n_hist, int32_t step, int32_t len_max_host,
+                                int32_t* d_state, int32_t step, int32_t len_max_host,
                                 float* S, float* F, int32_t* keep_idx, void* workspace, void* stream) {
-  if (!ctx || !qwin || !K || !V || !F_hist || !pos || !d_len || !d_n_hist || !S || !F || !keep_idx || step < 0)
+  if (!ctx || !qwin || !K || !V || !F_hist || !pos || !d_state || !S || !F || !keep_idx || step < 0)
     return GKV_ERR_INVALID_ARG;
   if (F == F_hist) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  st = gkv_score_window(ctx, qwin, K, d_len, step, len_max_host, S, workspace, stream);
+  st = gkv_score_window(ctx, qwin, K, d_state, step, len_max_host, S, workspace, stream);
   if (st != GKV_OK) return st;
-  st = gkv_global_update(ctx, S, F_hist, d_n_hist, d_len, len_max_host, F, stream);
+  st = gkv_global_update(ctx, S, F_hist, d_state, step, len_max_host, F, stream);
   if (st != GKV_OK) return st;
-  st = gkv_select_topk(ctx, F, d_len, len_max_host, keep_idx, workspace, stream);
+  st = gkv_select_topk(ctx, F, d_state, step, len_max_host, keep_idx, workspace, stream);
   if (st != GKV_OK) return st;
-  return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_len, d_n_hist, workspace, stream);
+  return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace, stream);
 }
 
 // ---- profiling API ------------------------------------------------------------------------------

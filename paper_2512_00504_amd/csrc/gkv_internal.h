@@ -6,8 +6,6 @@
 
 #include "gkv.h"
 
-#define GKV_WAVE 64
-
 // Dimensions every kernel needs, passed by value.
 struct GkvDims {
   int32_t L, B, Hq, Hkv, d, g;
@@ -26,16 +24,14 @@ struct gkv_ctx {
   int32_t attend_splits;  // 0 = automatic
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
-  bool mfma_ok;           // bf16, d == 128, g <= 16, w % 16 == 0
+  bool mfma_ok;           // bf16, d == 128, g <= 16
   GkvProfile* prof;
 };
 
 // Workspace layout (bytes from the base):
-//   [0, 4*L*B)                      len tickets (int32, self-resetting)
-//   [.., + 4*units)                 split tickets (int32, self-resetting)
+//   [0, 4*units)                    split tickets (int32, self-resetting)
 //   [.., + 4*units*splits*g*(d+2))  split-K partials (float)
 struct GkvWorkspace {
-  int32_t* len_ticket;
   int32_t* split_ticket;
   float* partials;
 };
@@ -45,7 +41,7 @@ static inline size_t gkv_align256(size_t x) { return (x + 255) & ~size_t(255); }
 int gkv_effective_splits(const gkv_ctx* ctx);
 GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base);
 
-// Launch record for profiling: the wrappers call this instead of <<< >>>.
+// Launch record for profiling: the wrappers launch through gkv_launch() below.
 struct GkvLaunch {
   gkv_ctx* ctx;
   int kernel_id;
@@ -55,26 +51,26 @@ struct GkvLaunch {
 // ---- launch wrappers implemented in the kernel files -------------------------------------
 struct AttendArgs {
   const void* q; const void* k_new; const void* v_new;
-  void* K; void* V; int32_t* pos; int32_t step; void* qwin; int32_t* d_len; void* out;
+  void* K; void* V; int32_t* pos; int32_t step; void* qwin; const int32_t* d_state; void* out;
   GkvWorkspace ws; int32_t splits; int32_t tile_keys;
 };
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);
 
 struct ScoreArgs {
-  const void* qwin; const void* K; const int32_t* d_len; int32_t step; float* S;
+  const void* qwin; const void* K; const int32_t* d_state; int32_t step; float* S;
 };
 hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a);
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a);
+bool gkv_score_mfma_supported(int g, int w);
 
 hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
-                                    const float* F_hist, const int32_t* d_n_hist,
-                                    const int32_t* d_len, float* F_out);
+                                    const float* F_hist, const int32_t* d_state, int32_t step, float* F_out);
 hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
-                                  const int32_t* d_len, int32_t* keep_idx);
+                                  const int32_t* d_state, int32_t step, int32_t* keep_idx);
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
-                              int32_t* d_len, int32_t* d_n_hist);
+                              int32_t* d_state, int32_t step);
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n);
 
 // Event bracketing for profiling (gkv_api.hip).  Returns the events to pass to
@@ -98,9 +94,29 @@ static inline hipError_t gkv_launch(const GkvLaunch& ln, F kernel, dim3 grid, di
   return hipGetLastError();
 }
 
-// Element offset of (row n, channel c) in one KV head's tiled K block; EPC = elements per 16 B.
+// The per-(layer, sequence) record of d_state, read with one 16-byte load.
+struct SeqState {
+  int32_t len, len_step, n_hist, n_tiled;
+};
+__device__ __forceinline__ SeqState load_state(const int32_t* d_state, int lb) {
+  const int4 v = *(const int4*)(d_state + 4 * (size_t)lb);
+  // the tiled prefix is whole tiles and never reaches past the stored length
+  int nt = v.w & ~15;
+  const int lim = (v.x > 0 ? v.x : 0) & ~15;
+  nt = nt < 0 ? 0 : (nt > lim ? lim : nt);
+  return SeqState{v.x, v.y, v.z, nt};
+}
+// Length before decode step `t` (every step since len_step appended one row), kept inside [0, cap].
+__device__ __forceinline__ int length_before_step(const SeqState& s, int t, int cap) {
+  const int l = s.len + (t - s.len_step);
+  return l < 0 ? 0 : (l > cap ? cap : l);
+}
+
+// Element offset of (row n, channel c) in one KV head's K block whose first n_tiled rows are in
+// tiled format; EPC = elements per 16 bytes.
 template <int EPC>
-__device__ __forceinline__ int k_tiled_offset(int n, int c, int d) {
+__device__ __forceinline__ int k_elem_offset(int n, int c, int d, int n_tiled) {
+  if (n >= n_tiled) return n * d + c;
   return (n >> 4) * 16 * d + (c / EPC) * (16 * EPC) + (n & 15) * EPC + (c % EPC);
 }
 

@@ -6,7 +6,7 @@
 
 namespace {
 
-// Dynamic LDS: float z[cap]; float rowmax[cap]; float sacc[cap]; float qs[d]; float red[8]; int misc[2]
+// Dynamic LDS: float z[cap]; float rowmax[cap]; float sacc[cap]; float qs[d]; float red[8]
 template <typename T>
 __global__ __launch_bounds__(256) void score_generic_kernel(GkvDims dm, ScoreArgs a) {
   extern __shared__ float smem[];
@@ -22,8 +22,9 @@ __global__ __launch_bounds__(256) void score_generic_kernel(GkvDims dm, ScoreArg
   float* qs = sacc + cap;
   float* red = qs + d;
 
-  const int l = a.d_len[lb];
-  if (l <= dm.b || l > cap) return;          // not above the budget: no compression for this sequence
+  const SeqState st = load_state(a.d_state, lb);
+  const int l = length_before_step(st, a.step + 1, cap);
+  if (l <= dm.b) return;                     // not above the budget: no compression for this sequence
   const int c = l - w;
   const T* Kh = (const T*)a.K + (size_t)unit * cap * d;
 
@@ -35,14 +36,14 @@ __global__ __launch_bounds__(256) void score_generic_kernel(GkvDims dm, ScoreArg
     for (int n = tid; n < c; n += blockDim.x) rowmax[n] = 0.f;
     for (int hi = 0; hi < g; ++hi) {
       const int head = j * g + hi;
-      const T* qh = (const T*)a.qwin + (((size_t)lb * dm.Hq + head) * w + slot) * d;
+      const T* qh = (const T*)a.qwin + (((size_t)lb * w + slot) * dm.Hq + head) * d;
       __syncthreads();
       for (int ch = tid; ch < d; ch += blockDim.x) qs[ch] = Elem<T>::ld(qh + ch);
       __syncthreads();
       float mx = -INFINITY;
       for (int n = tid; n < n_vis; n += blockDim.x) {
         float acc = 0.f;
-        for (int ch = 0; ch < d; ++ch) acc = fmaf(qs[ch], Elem<T>::ld(Kh + k_tiled_offset<EPC>(n, ch, d)), acc);
+        for (int ch = 0; ch < d; ++ch) acc = fmaf(qs[ch], Elem<T>::ld(Kh + k_elem_offset<EPC>(n, ch, d, st.n_tiled)), acc);
         acc *= dm.scale;
         z[n] = acc;
         mx = fmaxf(mx, acc);
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(256) void score_generic_kernel(GkvDims dm, ScoreArg
 
 hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a) {
   const int units = dm.L * dm.B * dm.Hkv;
-  const size_t shmem = sizeof(float) * (3 * (size_t)dm.cap + dm.d + 8) + 2 * sizeof(int);
+  const size_t shmem = sizeof(float) * (3 * (size_t)dm.cap + dm.d + 8);
   if (dtype == GKV_F32)
     return gkv_launch(ln, score_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);
   return gkv_launch(ln, score_generic_kernel<uint16_t>, dim3(units), dim3(256), shmem, dm, a);

@@ -25,6 +25,17 @@ constexpr int QSTR = ROW_BYTES + 16;       // padded LDS row of a staged query (
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// A operand of tile T: lane (row r, kblock kb) gets chunk 4c+kb of key 16T+r for c = 0..3; tiled
+// tiles are lane-contiguous, row-major tiles (rows appended since the last compaction) are not.
+__device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int T, int n_tiled,
+                                            int lane, int r, int kb) {
+  const bool tiled = 16 * T < n_tiled;
+  const char* p = Kh + (size_t)T * TILE_BYTES + (tiled ? lane * 16 : r * ROW_BYTES + kb * 16);
+  const int step_off = tiled ? 1024 : 64;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) kA[c] = ld16(p + c * step_off);
+}
+
 // Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float redM[NW*G*w]; float redS[NW*G*w]
 template <int NW, int G, int WT>
 __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
@@ -36,8 +47,9 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   constexpr int W = 16 * WT;
   constexpr int ROWS = G * W;
 
-  const int l = a.d_len[lb];
-  if (l <= dm.b || l > cap) return;
+  const SeqState seq = load_state(a.d_state, lb);
+  const int l = length_before_step(seq, a.step + 1, cap);
+  if (l <= dm.b) return;
   const int cc = l - W;                     // number of candidates
 
   char* qs = smem_raw;
@@ -52,9 +64,8 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     const int h = row / W, k = row % W;
     const int t_row = a.step - W + 1 + k;
     const int slot = ((t_row % W) + W) % W;
-    const size_t head = (size_t)lb * dm.Hq + j * G + h;
     *(u32x4*)(qs + row * QSTR + ch * 16) =
-        ld16((const char*)a.qwin + (head * W + slot) * (size_t)ROW_BYTES + ch * 16);
+        ld16((const char*)a.qwin + (((size_t)lb * W + slot) * dm.Hq + j * G + h) * (size_t)ROW_BYTES + ch * 16);
   }
   __syncthreads();
 
@@ -71,8 +82,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
 
   for (int T = wave; T < n_tiles; T += NW) {
     u32x4 kA[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) kA[c] = ld16(Kh + (size_t)T * TILE_BYTES + c * 1024 + lane * 16);
+    load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
     const int key_base = 16 * T + 4 * kb;
 #pragma unroll
     for (int h = 0; h < G; ++h)
@@ -143,8 +153,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   const float wf = (float)W;
   for (int T = wave; T < cand_tiles; T += NW) {
     u32x4 kA[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) kA[c] = ld16(Kh + (size_t)T * TILE_BYTES + c * 1024 + lane * 16);
+    load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
     f32x4 tot = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < WT; ++nt) {

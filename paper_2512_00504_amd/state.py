@@ -5,29 +5,37 @@ from __future__ import annotations
 
 import torch
 
-from .binding import Context, GkvConfig, make_config
+from .binding import ST_LEN, ST_LEN_STEP, ST_N_HIST, ST_N_TILED, Context, GkvConfig, make_config
 
 _TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
 
 
-def k_rows_to_tiled(K_rows: torch.Tensor) -> torch.Tensor:
-    """[..., cap, d] row-major -> the library's tiled K layout (same shape, permuted storage)."""
-    *lead, cap, d = K_rows.shape
-    epc = 16 // K_rows.element_size()
-    t = K_rows.reshape(*lead, cap // 16, 16, d // epc, epc)
-    n = len(lead)
-    t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
-    return t.reshape(*lead, cap, d)
+def k_rows_to_cache(K_rows: torch.Tensor, n_tiled: int) -> torch.Tensor:
+    """[..., cap, d] row-major -> the library's K layout with the first n_tiled rows tiled."""
+    n_tiled = n_tiled // 16 * 16
+    out = K_rows.clone()
+    if n_tiled:
+        *lead, cap, d = K_rows.shape
+        epc = 16 // K_rows.element_size()
+        t = K_rows[..., :n_tiled, :].reshape(*lead, n_tiled // 16, 16, d // epc, epc)
+        n = len(lead)
+        t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
+        out[..., :n_tiled, :] = t.reshape(*lead, n_tiled, d)
+    return out
 
 
-def k_tiled_to_rows(K_tiled: torch.Tensor) -> torch.Tensor:
-    """Inverse of k_rows_to_tiled."""
-    *lead, cap, d = K_tiled.shape
-    epc = 16 // K_tiled.element_size()
-    t = K_tiled.reshape(*lead, cap // 16, d // epc, 16, epc)
-    n = len(lead)
-    t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
-    return t.reshape(*lead, cap, d)
+def k_cache_to_rows(K_cache: torch.Tensor, n_tiled: int) -> torch.Tensor:
+    """Inverse of k_rows_to_cache."""
+    n_tiled = n_tiled // 16 * 16
+    out = K_cache.clone()
+    if n_tiled:
+        *lead, cap, d = K_cache.shape
+        epc = 16 // K_cache.element_size()
+        t = K_cache[..., :n_tiled, :].reshape(*lead, n_tiled // 16, d // epc, 16, epc)
+        n = len(lead)
+        t = t.permute(*range(n), n, n + 2, n + 1, n + 3).contiguous()
+        out[..., :n_tiled, :] = t.reshape(*lead, n_tiled, d)
+    return out
 
 
 class DecodeState:
@@ -44,12 +52,11 @@ class DecodeState:
         dev = torch.device(device)
         self.device = dev
         z = lambda *s, dtype: torch.zeros(*s, dtype=dtype, device=dev)
-        self.K = z(L, B, Hkv, cap, d, dtype=dt)          # tiled layout
+        self.K = z(L, B, Hkv, cap, d, dtype=dt)          # rows below N_TILED tiled, the rest row-major
         self.V = z(L, B, Hkv, cap, d, dtype=dt)
         self.pos = torch.full((L, B, Hkv, cap), -1, dtype=torch.int32, device=dev)
-        self.qwin = z(L, B, Hq, w, d, dtype=dt)
-        self.d_len = z(L, B, dtype=torch.int32)
-        self.d_n_hist = z(L, B, dtype=torch.int32)
+        self.qwin = z(L, B, w, Hq, d, dtype=dt)
+        self.d_state = z(L, B, 4, dtype=torch.int32)     # {len, len_step, n_hist, n_tiled}
         self.F_hist = z(L, B, Hkv, cap, dtype=torch.float32)
         self.S = z(L, B, Hkv, cap, dtype=torch.float32)
         self.F = z(L, B, Hkv, cap, dtype=torch.float32)
@@ -67,48 +74,58 @@ class DecodeState:
         kw.update(over)
         return cls(make_config(**kw), device=device, params=params)
 
+    # lengths as the kernels see them ---------------------------------------------------------
+    def lengths(self, next_step: int) -> torch.Tensor:
+        """[L,B] cache lengths before decode step `next_step` (LEN + next_step - LEN_STEP)."""
+        return self.d_state[..., ST_LEN] + (next_step - self.d_state[..., ST_LEN_STEP])
+
+    def set_state(self, length, len_step, n_hist, n_tiled):
+        """Fill every (layer, sequence) record with the same values."""
+        self.d_state[..., ST_LEN] = length
+        self.d_state[..., ST_LEN_STEP] = len_step
+        self.d_state[..., ST_N_HIST] = n_hist
+        self.d_state[..., ST_N_TILED] = n_tiled
+        self.len_host = int(length)
+
     def load_prefix(self, k, v, t0=0):
         """Place tokens t0..t0+n-1 (k, v: [n, L, B, h_kv, d]) as cache rows 0..n-1 with positions
-        t0..t0+n-1.  For n <= budget this is exactly the state n appending decode steps leave
-        behind (nothing is evicted before the cache exceeds the budget); pure data placement."""
+        t0..t0+n-1, K row-major (N_TILED = 0).  For n <= budget this is exactly the state n
+        appending decode steps leave behind (nothing is evicted before the cache exceeds the
+        budget); pure data placement."""
         n = k.shape[0]
         assert n <= self.cfg.budget
-        rows = torch.zeros_like(self.V)
-        rows[..., :n, :] = k.to(self.V.dtype).permute(1, 2, 3, 0, 4)
-        self.K.copy_(k_rows_to_tiled(rows))
-        rows[..., :n, :] = v.to(self.V.dtype).permute(1, 2, 3, 0, 4)
-        self.V.copy_(rows)
+        self.K.zero_(); self.V.zero_()
+        self.K[..., :n, :] = k.to(self.V.dtype).permute(1, 2, 3, 0, 4)
+        self.V[..., :n, :] = v.to(self.V.dtype).permute(1, 2, 3, 0, 4)
         self.pos.fill_(-1)
         self.pos[..., :n] = torch.arange(t0, t0 + n, dtype=torch.int32, device=self.device)
-        self.d_len.fill_(n)
-        self.d_n_hist.fill_(0)
-        self.len_host = n
+        self.set_state(n, t0 + n, 0, 0)
 
     # one call each -------------------------------------------------------------------------
     def attend_decode(self, q, k_new, v_new, step):
-        self.ctx.attend_decode(q, k_new, v_new, self.K, self.V, self.pos, step, self.qwin, self.d_len,
+        self.ctx.attend_decode(q, k_new, v_new, self.K, self.V, self.pos, step, self.qwin, self.d_state,
                                self.len_host, self.out, self.workspace)
         if k_new is not None:
             self.len_host += 1
         return self.out
 
     def score_window(self, step):
-        self.ctx.score_window(self.qwin, self.K, self.d_len, step, self.len_host, self.S, self.workspace)
+        self.ctx.score_window(self.qwin, self.K, self.d_state, step, self.len_host, self.S, self.workspace)
 
-    def global_update(self):
-        self.ctx.global_update(self.S, self.F_hist, self.d_n_hist, self.d_len, self.len_host, self.F)
+    def global_update(self, step):
+        self.ctx.global_update(self.S, self.F_hist, self.d_state, step, self.len_host, self.F)
 
-    def select_topk(self):
-        self.ctx.select_topk(self.F, self.d_len, self.len_host, self.keep_idx, self.workspace)
+    def select_topk(self, step):
+        self.ctx.select_topk(self.F, self.d_state, step, self.len_host, self.keep_idx, self.workspace)
 
-    def compact(self):
-        self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_len,
-                         self.d_n_hist, self.workspace)
+    def compact(self, step):
+        self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_state, step,
+                         self.workspace)
         if self.len_host > self.cfg.budget:
             self.len_host = self.cfg.budget
 
     def evict(self, step):
-        self.ctx.evict(self.qwin, self.K, self.V, self.F_hist, self.pos, self.d_len, self.d_n_hist, step,
+        self.ctx.evict(self.qwin, self.K, self.V, self.F_hist, self.pos, self.d_state, step,
                        self.len_host, self.S, self.F, self.keep_idx, self.workspace)
         if self.len_host > self.cfg.budget:
             self.len_host = self.cfg.budget

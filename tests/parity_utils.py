@@ -8,7 +8,7 @@ import torch
 
 from gkv_traces import Trace
 from oracle import gkv_oracle as O
-from paper_2512_00504_amd.state import DecodeState, k_rows_to_tiled, k_tiled_to_rows
+from paper_2512_00504_amd.state import DecodeState, k_cache_to_rows, k_rows_to_cache
 
 TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 # output tolerance: 1e-5 relative (to the row's largest magnitude) for fp32, 2e-2 absolute for bf16
@@ -65,16 +65,17 @@ def check_keep(keep_gpu, keep_ref, F_ref, what=""):
     return len(only_gpu)
 
 
-def upload_oracle_state(st: DecodeState, orc, l, b):
-    """Overwrite the GPU state of (layer l, sequence b) with the oracle's (teacher forcing)."""
+def upload_oracle_state(st: DecodeState, orc, l, b, next_step):
+    """Overwrite the GPU state of (layer l, sequence b) with the oracle's (teacher forcing);
+    `next_step` is the index of the decode step that comes next."""
     dt = st.K.dtype
     dev = st.device
-    st.K[l, b] = k_rows_to_tiled(torch.from_numpy(orc.K).to(dt)).to(dev)
+    n_tiled = int(st.d_state[l, b, 3])
+    st.K[l, b] = k_rows_to_cache(torch.from_numpy(orc.K).to(dt), n_tiled).to(dev)
     st.V[l, b] = torch.from_numpy(orc.V).to(dt).to(dev)
     st.pos[l, b] = torch.from_numpy(orc.pos).to(torch.int32).to(dev)
     st.F_hist[l, b] = torch.from_numpy(orc.F_hist).to(torch.float32).to(dev)
-    st.d_len[l, b] = orc.len
-    st.d_n_hist[l, b] = orc.n_hist
+    st.d_state[l, b] = torch.tensor([orc.len, next_step, orc.n_hist, n_tiled], dtype=torch.int32)
 
 
 def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_every_event=True,
@@ -106,7 +107,7 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                 if fused_evict:
                     st.evict(t)
                 else:
-                    st.score_window(t); st.global_update(); st.select_topk(); st.compact()
+                    st.score_window(t); st.global_update(t); st.select_topk(t); st.compact(t)
                 ev_gpu = dict(S=st.S.cpu().numpy(), F=st.F.cpu().numpy(), keep=st.keep_idx.cpu().numpy())
             for (l, b), orc in orcs.items():
                 n_ev = len(orc.events)
@@ -128,27 +129,29 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                         swapped += check_keep(ev_gpu["keep"][l, b, j], ev["keep"][j], ev["F"][j], "keep " + what)
                     stats["swaps"] += swapped
                     if swapped:
-                        upload_oracle_state(st, orc, l, b)
+                        upload_oracle_state(st, orc, l, b, t + 1)
                     elif check_state_every_event:
-                        check_state(st, orc, l, b, f"state t={t} pair=({l},{b})")
+                        check_state(st, orc, l, b, t + 1, f"state t={t} pair=({l},{b})")
                 elif ev_gpu is not None:
                     raise AssertionError(f"GPU host trigger fired at t={t} but the oracle did not compress")
             if ev_gpu is not None:
                 stats["events"] += 1
     for (l, b), orc in orcs.items():
-        check_state(st, orc, l, b, f"final state pair=({l},{b})")
+        check_state(st, orc, l, b, n_steps, f"final state pair=({l},{b})")
     stats["state"] = st
     stats["oracles"] = orcs
     return stats
 
 
-def check_state(st: DecodeState, orc, l, b, what=""):
-    """Cache contents after compaction: lengths, positions, K, V bit-exact; F_hist to fp32 accuracy."""
+def check_state(st: DecodeState, orc, l, b, next_step, what=""):
+    """Cache contents: length, positions, K, V bit-exact; F_hist to fp32 accuracy."""
     n = orc.len
-    assert int(st.d_len[l, b]) == n, f"{what}: len {int(st.d_len[l, b])} != {n}"
-    assert int(st.d_n_hist[l, b]) == orc.n_hist, what
+    rec = st.d_state[l, b].cpu().tolist()
+    got = rec[0] + (next_step - rec[1])
+    assert got == n, f"{what}: len {got} != {n}"
+    assert rec[2] == orc.n_hist, what
     np.testing.assert_array_equal(st.pos[l, b, :, :n].cpu().numpy(), orc.pos[:, :n], err_msg=what)
-    Kg = k_tiled_to_rows(st.K[l, b])[:, :n].double().cpu().numpy()
+    Kg = k_cache_to_rows(st.K[l, b], rec[3])[:, :n].double().cpu().numpy()
     Vg = st.V[l, b, :, :n].double().cpu().numpy()
     np.testing.assert_array_equal(Kg, orc.K[:, :n], err_msg=what + " K")
     np.testing.assert_array_equal(Vg, orc.V[:, :n], err_msg=what + " V")

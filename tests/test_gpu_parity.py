@@ -8,7 +8,7 @@ import torch
 from gkv_traces import CONFIGS
 from oracle import gkv_oracle as O
 from paper_2512_00504_amd import make_config
-from paper_2512_00504_amd.state import DecodeState, k_rows_to_tiled, k_tiled_to_rows
+from paper_2512_00504_amd.state import DecodeState, k_cache_to_rows, k_rows_to_cache
 
 from parity_utils import check_keep, check_scores, run_parity
 
@@ -120,20 +120,57 @@ def _state(dtype="f32", **kw):
     return DecodeState(make_config(**base))
 
 
-def test_attend_ragged_lengths_and_empty_append():
-    st = _state()
+def _set_lengths(st, lens, step_next, n_hist=(0, 0), n_tiled=(0, 0)):
+    """d_state for a 1-layer, 2-sequence state: lengths `lens` before decode step `step_next`."""
+    rec = [[lens[i], step_next, n_hist[i], n_tiled[i]] for i in range(2)]
+    st.d_state.copy_(torch.tensor([rec], dtype=torch.int32))
+    st.len_host = max(lens)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attend_ragged_lengths_formats_and_empty_append(dtype):
+    kw = {} if dtype == "f32" else dict(head_dim=128, n_q_heads=14, n_kv_heads=2)
+    st = _state(dtype, **kw)
+    d, hq = st.cfg.head_dim, st.cfg.n_q_heads
     g = torch.Generator().manual_seed(1)
-    K = torch.randn(1, 2, 2, 64, 64, generator=g); V = torch.randn(1, 2, 2, 64, 64, generator=g)
-    q = torch.randn(1, 2, 4, 64, generator=g)
-    st.K.copy_(k_rows_to_tiled(K)); st.V.copy_(V)
-    st.d_len.copy_(torch.tensor([[5, 37]], dtype=torch.int32)); st.len_host = 37
+    K = torch.randn(1, 2, 2, 64, d, generator=g).to(st.K.dtype)
+    V = torch.randn(1, 2, 2, 64, d, generator=g).to(st.K.dtype)
+    q = torch.randn(1, 2, hq, d, generator=g).to(st.K.dtype)
+    # sequence 0: 5 rows, all row-major; sequence 1: 37 rows, the first 32 in tiled format
+    st.K[0, 0] = K[0, 0].cuda(); st.K[0, 1] = k_rows_to_cache(K[0, 1], 32).cuda(); st.V.copy_(V)
+    _set_lengths(st, (5, 37), step_next=3, n_tiled=(0, 32))
+    state0 = st.d_state.clone()
     out = st.attend_decode(q.cuda(), None, None, 3).double().cpu().numpy()
-    assert st.d_len.cpu().tolist() == [[5, 37]]                   # no append: lengths unchanged
+    assert torch.equal(st.d_state, state0)                        # the decode kernel never writes lengths
+    tol = 1e-5 if dtype == "f32" else None
     for b, n in enumerate((5, 37)):
-        ref = O.attend(q[0, b].numpy(), K[0, b].numpy(), V[0, b].numpy(), n)
+        ref = O.attend(q[0, b].double().numpy(), K[0, b].double().numpy(), V[0, b].double().numpy(), n)
+        if tol:
+            np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=tol * np.abs(ref).max())
+        else:
+            np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=2e-2)
+    # window ring slot 3 now holds q (ring layout [L, B, w, h_q, d])
+    assert torch.equal(st.qwin[0, :, 3].cpu(), q[0])
+
+
+def test_attend_length_follows_the_step_number():
+    # LEN = 5 before step 10: at step 12 the cache holds 7 rows and row 7 is appended
+    st = _state()
+    g = torch.Generator().manual_seed(2)
+    K = torch.randn(1, 2, 2, 64, 64, generator=g); V = torch.randn(1, 2, 2, 64, 64, generator=g)
+    q = torch.randn(1, 2, 4, 64, generator=g); kn = torch.randn(1, 2, 2, 64, generator=g); vn = torch.randn(1, 2, 2, 64, generator=g)
+    st.K.copy_(K); st.V.copy_(V)
+    _set_lengths(st, (5, 5), step_next=10)
+    st.len_host = 7
+    out = st.attend_decode(q.cuda(), kn.cuda(), vn.cuda(), 12).double().cpu().numpy()
+    K2, V2 = K.clone(), V.clone()
+    K2[0, :, :, 7] = kn[0]; V2[0, :, :, 7] = vn[0]
+    for b in range(2):
+        ref = O.attend(q[0, b].numpy(), K2[0, b].numpy(), V2[0, b].numpy(), 8)
         np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=1e-5 * np.abs(ref).max())
-    # window ring slot 3 now holds q
-    np.testing.assert_array_equal(st.qwin[0, :, :, 3].cpu().numpy(), q[0].numpy())
+    assert torch.equal(st.K[0, :, :, 7].cpu(), kn[0]) and torch.equal(st.V[0, :, :, 7].cpu(), vn[0])
+    assert (st.pos[0, :, :, 7] == 12).all()
+    assert torch.equal(st.qwin[0, :, 12 % 4].cpu(), q[0])
 
 
 def test_attend_rejects_bad_arguments():
@@ -147,10 +184,10 @@ def test_attend_rejects_bad_arguments():
     assert e.value.status == 6
     st.len_host = 0
     with pytest.raises(GkvError) as e:
-        st.ctx.attend_decode(q, kv, None, st.K, st.V, st.pos, 0, st.qwin, st.d_len, 0, st.out, st.workspace)
+        st.ctx.attend_decode(q, kv, None, st.K, st.V, st.pos, 0, st.qwin, st.d_state, 0, st.out, st.workspace)
     assert e.value.status == 1
     with pytest.raises(GkvError) as e:
-        st.ctx.attend_decode(q, kv, kv, st.K, st.V, st.pos, 0, st.qwin, st.d_len, 0, st.out, None)
+        st.ctx.attend_decode(q, kv, kv, st.K, st.V, st.pos, 0, st.qwin, st.d_state, 0, st.out, None)
     assert e.value.status == 3
 
 
@@ -163,7 +200,7 @@ def test_score_window_closed_form_equal_keys():
         l = st.cfg.budget + st.cfg.interval - 3
         st.K.fill_(0.5)
         st.qwin.copy_(torch.randn(st.qwin.shape).to(st.qwin.dtype))
-        st.d_len.fill_(l); st.len_host = l
+        _set_lengths(st, (l, l), step_next=l, n_tiled=(0, 32))     # constant keys: format does not matter
         st.score_window(step=l - 1)
         c = l - w
         expect = sum(1.0 / (c + k + 1) for k in range(w)) / w
@@ -173,12 +210,12 @@ def test_score_window_closed_form_equal_keys():
 
 def test_eviction_is_a_noop_at_or_below_budget():
     st = _state()
-    st.d_len.copy_(torch.tensor([[32, 40]], dtype=torch.int32)); st.len_host = 40
+    _set_lengths(st, (32, 40), step_next=40)
     st.K.copy_(torch.randn(st.K.shape)); st.V.copy_(torch.randn(st.V.shape))
     st.qwin.copy_(torch.randn(st.qwin.shape))
     K0, V0 = st.K.clone(), st.V.clone()
     st.evict(step=39)
-    assert st.d_len.cpu().tolist() == [[32, 32]] and st.d_n_hist.cpu().tolist() == [[0, 28]]
+    assert st.d_state.cpu().tolist() == [[[32, 40, 0, 0], [32, 40, 28, 32]]]
     assert torch.equal(st.K[0, 0], K0[0, 0]) and torch.equal(st.V[0, 0], V0[0, 0])     # sequence 0 untouched
     assert not torch.equal(st.V[0, 1], V0[0, 1])
 
@@ -192,9 +229,8 @@ def test_global_update_three_forms_against_oracle():
         S = rng.random((1, 2, 2, 64)).astype(np.float32) ** 3
         H = rng.random((1, 2, 2, 64)).astype(np.float32)
         st.S.copy_(torch.from_numpy(S)); st.F_hist.copy_(torch.from_numpy(H))
-        st.d_len.fill_(l); st.len_host = l
-        st.d_n_hist.copy_(torch.tensor([[0, 28]], dtype=torch.int32))
-        st.global_update()
+        _set_lengths(st, (l, l), step_next=l, n_hist=(0, 28))
+        st.global_update(l - 1)
         F = st.F.cpu().numpy()
         for b, nh in enumerate((0, 28)):
             ref = O.global_score(S[0, b].astype(np.float64), H[0, b].astype(np.float64), nh, 0.8, form, n_cand=c)
@@ -205,7 +241,7 @@ def test_select_topk_ties_nan_and_brute_force():
     st = _state()
     l, w, k = 40, 4, 28
     c = l - w
-    st.d_len.fill_(l); st.len_host = l
+    _set_lengths(st, (l, l), step_next=l)
     rng = np.random.default_rng(6)
     F = np.zeros((1, 2, 2, 64), np.float32)
     F[0, 0, 0, :c] = 0.25                                   # all tied: first k indices
@@ -213,7 +249,7 @@ def test_select_topk_ties_nan_and_brute_force():
     F[0, 1, 0, :c] = rng.random(c)
     F[0, 1, 1, :c] = rng.random(c); F[0, 1, 1, 3] = np.nan; F[0, 1, 1, 7] = np.inf; F[0, 1, 1, 9] = -0.0
     st.F.copy_(torch.from_numpy(F))
-    st.select_topk()
+    st.select_topk(l - 1)
     keep = st.keep_idx.cpu().numpy()
     assert keep[0, 0, 0].tolist() == list(range(k))
     for (b, j) in ((0, 1), (1, 0)):
@@ -225,8 +261,8 @@ def test_select_topk_ties_nan_and_brute_force():
 
 
 @pytest.mark.parametrize("pattern", ["front", "back", "alternate", "random"])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_compact_adversarial_keep_patterns(pattern, dtype):
+@pytest.mark.parametrize("dtype,nt_old", [("f32", 0), ("bf16", 0), ("bf16", 160), ("f32", 96)])
+def test_compact_adversarial_keep_patterns(pattern, dtype, nt_old):
     kw = {} if dtype == "f32" else dict(head_dim=128)
     st = _state(dtype, budget=160, window=8, interval=32, capacity=192, **kw)
     b, w, l = 160, 8, 192
@@ -245,12 +281,13 @@ def test_compact_adversarial_keep_patterns(pattern, dtype):
     K = torch.randn(st.K.shape).to(st.K.dtype); V = torch.randn(st.V.shape).to(st.V.dtype)
     pos = torch.arange(192, dtype=torch.int32).expand(1, 2, 2, 192).contiguous() + 1000
     F = torch.rand(1, 2, 2, 192)
-    st.K.copy_(k_rows_to_tiled(K)); st.V.copy_(V); st.pos.copy_(pos); st.F.copy_(F)
+    # the first nt_old rows start in tiled format, the rest row-major (as appended)
+    st.K.copy_(k_rows_to_cache(K, nt_old)); st.V.copy_(V); st.pos.copy_(pos); st.F.copy_(F)
     st.keep_idx.copy_(torch.from_numpy(keep_all))
-    st.d_len.fill_(l); st.len_host = l
-    st.compact()
-    assert st.d_len.cpu().tolist() == [[b, b]] and st.d_n_hist.cpu().tolist() == [[k, k]]
-    Kr = k_tiled_to_rows(st.K).cpu()
+    _set_lengths(st, (l, l), step_next=500, n_tiled=(nt_old, nt_old))
+    st.compact(step=499)
+    assert st.d_state.cpu().tolist() == [[[b, 500, k, 160], [b, 500, k, 160]]]
+    Kr = k_cache_to_rows(st.K, 160).cpu()
     for bb in range(2):
         for j in range(2):
             src = np.concatenate([keep_all[0, bb, j], np.arange(c, l)])

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import paper_2512_00504_amd as P
-from paper_2512_00504_amd.state import k_rows_to_tiled, k_tiled_to_rows
+from paper_2512_00504_amd.state import k_cache_to_rows, k_rows_to_cache
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -56,7 +56,7 @@ def test_create_validates_configuration():
            dict(dtype=3), dict(combine=5),
            dict(capacity=64),               # < b + s
            dict(capacity=100),              # not a multiple of 32
-           dict(head_dim=62)]
+           dict(head_dim=62), dict(head_dim=512)]
     for kw in bad:
         with pytest.raises(P.GkvError):
             P.Context(_cfg(**kw))
@@ -71,9 +71,10 @@ def test_calls_reject_null_pointers_without_a_gpu():
     n = ctypes.c_void_p(None)
     assert lib.gkv_attend_decode(ctx.h, n, n, n, n, n, n, 0, n, n, 0, n, n, n) == 1
     assert lib.gkv_score_window(ctx.h, n, n, n, 0, 0, n, n, n) == 1
-    assert lib.gkv_global_update(ctx.h, n, n, n, n, 0, n, n) == 1
-    assert lib.gkv_select_topk(ctx.h, n, n, 0, n, n, n) == 1
-    assert lib.gkv_compact(ctx.h, n, n, n, n, n, n, n, n, n, n) == 1
+    assert lib.gkv_global_update(ctx.h, n, n, n, 0, 0, n, n) == 1
+    assert lib.gkv_select_topk(ctx.h, n, n, 0, 0, n, n, n) == 1
+    assert lib.gkv_compact(ctx.h, n, n, n, n, n, n, n, 0, n, n) == 1
+    assert lib.gkv_evict(ctx.h, n, n, n, n, n, n, 0, 0, n, n, n, n, n) == 1
     assert lib.gkv_set_param(ctx.h, b"no_such_knob", 1) == 1
 
 
@@ -98,17 +99,18 @@ def test_memory_accounting_reproduces_the_papers_appendix():
         assert sc_b / kv_b == pytest.approx(g["score_fraction_approx"], rel=0.04)
 
 
-def test_k_offset_matches_the_tiling_permutation():
-    for dtype, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+def test_k_offset_matches_the_layout_permutation():
+    for dtype, tdt, idt in (("bf16", torch.bfloat16, torch.int16), ("f32", torch.float32, torch.int32)):
         cfg = _cfg(dtype=dtype, head_dim=64, capacity=96)
-        rows = torch.arange(96 * 64, dtype=torch.float32).reshape(96, 64).to(tdt)      # exact in bf16? use ids below
-        ids = torch.arange(96 * 64, dtype=torch.int32).reshape(96, 64)
-        flat = k_rows_to_tiled(ids.view(tdt) if tdt == torch.float32 else ids.to(torch.int16).view(tdt))
-        flat_ids = (flat.view(torch.int32) if tdt == torch.float32 else flat.view(torch.int16)).reshape(-1)
-        for (r, c) in ((0, 0), (1, 0), (15, 63), (16, 0), (17, 9), (95, 63), (40, 7), (40, 8)):
-            off = P.k_offset(cfg, r, c)
-            assert int(flat_ids[off]) == r * 64 + c
-        back = k_tiled_to_rows(flat)
-        assert torch.equal(back.view(torch.int32) if tdt == torch.float32 else back.view(torch.int16),
-                           ids if tdt == torch.float32 else ids.to(torch.int16))
-    assert P.k_offset(_cfg(), -1, 0) == -1 and P.k_offset(_cfg(), 0, 64) == -1
+        ids = torch.arange(96 * 64, dtype=torch.int32).reshape(96, 64).to(idt)      # 6144 ids fit in int16
+        for n_tiled in (0, 32, 96):
+            cache = k_rows_to_cache(ids.view(tdt), n_tiled)
+            flat = cache.view(idt).reshape(-1)
+            for (r, c) in ((0, 0), (1, 0), (15, 63), (16, 0), (17, 9), (31, 8), (32, 0), (40, 7), (40, 8), (95, 63)):
+                off = P.k_offset(cfg, r, c, n_tiled)
+                assert int(flat[off]) == r * 64 + c, (dtype, n_tiled, r, c)
+            assert torch.equal(k_cache_to_rows(cache, n_tiled).view(idt), ids)
+    # row 17, channel 9 of a bf16 d=64 block: tile 1 (1024) + chunk 1 (128) + row 1 (8) + 1
+    assert P.k_offset(_cfg(dtype="bf16"), 17, 9, 32) == 1024 + 128 + 8 + 1
+    assert P.k_offset(_cfg(dtype="bf16"), 17, 9, 16) == 17 * 64 + 9
+    assert P.k_offset(_cfg(), -1, 0, 0) == -1 and P.k_offset(_cfg(), 0, 64, 0) == -1
