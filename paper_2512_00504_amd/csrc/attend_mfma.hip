@@ -102,6 +102,7 @@ template <int KT, bool EDGE>
 __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const bf16x8 (&qB)[4], int it,
                                               float scale_log2, int r, int kb, bool has_new, int len0,
                                               int n_tot, const char* knew, const char* vnew) {
+  // knew / vnew: the newest token's k and v rows, staged in LDS at the start of the workgroup
   constexpr int NS = 4 * KT;
   const int key0 = it * 16 * KT;
   if constexpr (EDGE) {
@@ -111,12 +112,12 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
       for (int tt = 0; tt < KT; ++tt)
         if (tt == tt_new && r == rr) {
 #pragma unroll
-          for (int c = 0; c < 4; ++c) s.kA[tt][c] = ld16(knew + (4 * c + kb) * 16);
+          for (int c = 0; c < 4; ++c) s.kA[tt][c] = *(const u32x4*)(knew + (4 * c + kb) * 16);
         }
 #pragma unroll
       for (int jj = 0; jj < NS; ++jj) {
         const int key = key0 + (jj & 3) + 4 * kb + (jj >> 2) * 16;
-        if (key == len0) s.vR[jj] = ld16(vnew + r * 16);
+        if (key == len0) s.vR[jj] = *(const u32x4*)(vnew + r * 16);
       }
     }
 #pragma unroll
@@ -216,14 +217,12 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   const char* Vh = (const char*)a.V + (size_t)unit * cap * ROW_BYTES;
   const int stride = splits * NW;
 
-  // The length comes from the state record and the step number; nothing is written back, so
-  // the workgroups of a (layer, sequence) need no ordering among themselves.
-  const SeqState seq = load_state(a.d_state, lb);
-  const int len0 = length_before_step(seq, a.step, cap);
-  const bool has_new = (a.k_new != nullptr) && (len0 < cap);
-  const int n_tot = len0 + (has_new ? 1 : 0);
-
-  // B operand of the QK product: lane (head r, kblock kb) holds channels [8*(4c+kb), +8) of q[r]
+  // Requests whose addresses do not depend on the state record go out first: the group's
+  // queries (B operand of the QK product: lane (head r, kblock kb) holds channels
+  // [8*(4c+kb), +8) of q[r]) and the rows stored at the end of the workgroup, one 16-byte piece
+  // per thread and round: pieces [0,16) k_new, [16,32) v_new (every workgroup: the wavefront
+  // that owns the last slice substitutes them for cache row `len`), [32, 32 + 16 g) the group's
+  // q rows for the window ring (split 0 only).
   bf16x8 qB[4];
   {
     const char* qh = (const char*)a.q + ((size_t)lb * dm.Hq + j * g + r) * ROW_BYTES;
@@ -234,23 +233,31 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
       qB[c] = as_bf16x8(v);
     }
   }
-  const char* knew = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
-  const char* vnew = (const char*)a.v_new + (size_t)unit * ROW_BYTES;
-  // What this workgroup stores at the end besides the output (split 0 only), one 16-byte piece
-  // per thread and round: pieces [0,16) k_new, [16,32) v_new, [32, 32 + 16 g) the group's q rows
-  // for the window ring.  Requested now so that the latency is long gone by then.
   constexpr int AP_ROUNDS = (32 + 16 * 16 + NW * 64 - 1) / (NW * 64);
   u32x4 ap[AP_ROUNDS];
   const bool appender = sp == 0;
-  if (appender) {
+  const bool may_grow = a.k_new != nullptr;
+  {
+    const char* knew_g = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
+    const char* vnew_g = (const char*)a.v_new + (size_t)unit * ROW_BYTES;
 #pragma unroll
     for (int rd = 0; rd < AP_ROUNDS; ++rd) {
       const int x = tid + rd * NW * 64;
-      if (x < 16) { if (has_new) ap[rd] = ld16(knew + x * 16); }
-      else if (x < 32) { if (has_new) ap[rd] = ld16(vnew + (x - 16) * 16); }
-      else if (x < 32 + 16 * g) ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16);
+      ap[rd] = u32x4{0u, 0u, 0u, 0u};
+      if (x < 16) { if (may_grow) ap[rd] = ld16(knew_g + x * 16); }
+      else if (x < 32) { if (may_grow) ap[rd] = ld16(vnew_g + (x - 16) * 16); }
+      else if (x < 32 + 16 * g) {
+        if (appender) ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16);
+      }
     }
   }
+
+  // The length comes from the state record and the step number; nothing is written back, so
+  // the workgroups of a (layer, sequence) need no ordering among themselves.
+  const SeqState seq = load_state(a.d_state, lb);
+  const int len0 = length_before_step(seq, a.step, cap);
+  const bool has_new = may_grow && (len0 < cap);
+  const int n_tot = len0 + (has_new ? 1 : 0);
   const float scale_log2 = dm.scale * 1.4426950408889634f;
 
   Running st;
@@ -259,12 +266,27 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
 #pragma unroll
   for (int m = 0; m < 8; ++m) st.oacc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // First slice in flight, then stage k_new / v_new in LDS for whoever owns the last slice.
   const int n_iter = (n_tot + KEYS - 1) / KEYS;
-  for (int it = sp * NW + wave; it < n_iter; it += stride) {
-    Slice<KT> s;
-    issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
+  int it = sp * NW + wave;
+  Slice<KT> s;
+  if (it < n_iter) issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
+  // stage: 16-byte pieces [0,16) k_new, [16,32) v_new, [32, 32+16g) q rows; kept in LDS, not in
+  // registers, until they are stored at the end
+  char* stage = (char*)(smem + NW * g * OSTR + NW * 16 + NW * 64);
+  const char* knew = stage;
+  const char* vnew = stage + ROW_BYTES;
+#pragma unroll
+  for (int rd = 0; rd < AP_ROUNDS; ++rd) {
+    const int x = tid + rd * NW * 64;
+    if (x < 32 + 16 * g) *(u32x4*)(stage + x * 16) = ap[rd];
+  }
+  __syncthreads();
+  while (it < n_iter) {
     if ((it + 1) * KEYS > len0) process_slice<KT, true>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
     else process_slice<KT, false>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    it += stride;
+    if (it < n_iter) issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
   }
   const float m_run = st.m_run, l_run = st.l_run;
   f32x4 (&oacc)[8] = st.oacc;
@@ -323,12 +345,14 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
 #pragma unroll
     for (int rd = 0; rd < AP_ROUNDS; ++rd) {
       const int x = tid + rd * NW * 64;
+      if (x >= 32 + 16 * g) continue;
+      const u32x4 piece = *(const u32x4*)(stage + x * 16);
       if (x < 16) {
-        if (has_new) *(u32x4*)((char*)a.K + ((size_t)unit * cap + len0) * ROW_BYTES + x * 16) = ap[rd];
+        if (has_new) *(u32x4*)((char*)a.K + ((size_t)unit * cap + len0) * ROW_BYTES + x * 16) = piece;
       } else if (x < 32) {
-        if (has_new) *(u32x4*)((char*)a.V + ((size_t)unit * cap + len0) * ROW_BYTES + (x - 16) * 16) = ap[rd];
-      } else if (x < 32 + 16 * g) {
-        *(u32x4*)((char*)a.qwin + (((size_t)lb * dm.w + slot) * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16) = ap[rd];
+        if (has_new) *(u32x4*)((char*)a.V + ((size_t)unit * cap + len0) * ROW_BYTES + (x - 16) * 16) = piece;
+      } else {
+        *(u32x4*)((char*)a.qwin + (((size_t)lb * dm.w + slot) * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16) = piece;
       }
     }
     if (has_new && tid == NW * 64 - 1) a.pos[(size_t)unit * cap + len0] = a.step;
@@ -373,7 +397,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a) {
   constexpr int NW = 4;
   const int units = dm.L * dm.B * dm.Hkv;
-  const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 64);
+  const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 64) + (32 + 16 * dm.g) * 16;
   if (a.tile_keys == 32)
     return gkv_launch(ln, attend_mfma_kernel<NW, 2>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
   return gkv_launch(ln, attend_mfma_kernel<NW, 1>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
