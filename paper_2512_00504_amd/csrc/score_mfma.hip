@@ -25,6 +25,19 @@ constexpr int QSTR = ROW_BYTES + 16;       // padded LDS row of a staged query (
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// e^x for x <= 0 to about 1.5 ulp in ~6 instructions: x*log2(e) is formed as an unevaluated
+// sum hi + lo (lo carries the rounding of the product and the low bits of log2 e), the hardware
+// exp2 takes hi, and 2^lo is applied as 1 + lo*ln2.  The plain library expf costs ~20.
+__device__ __forceinline__ float exp_fast(float x) {
+  x = fmaxf(x, -200.f);                                     // e^-200 is 0 in fp32; keeps -inf out of the fma
+  const float L2E_HI = 1.44269502162933349609375f;          // float(log2 e)
+  const float L2E_LO = 1.925963033500837e-8f;               // log2 e - L2E_HI
+  const float hi = x * L2E_HI;
+  const float lo = fmaf(x, L2E_HI, -hi) + x * L2E_LO;
+  const float e = __builtin_amdgcn_exp2f(hi);
+  return fmaf(e, lo * 0.693147180559945f, e);
+}
+
 // A operand of tile T: lane (row r, kblock kb) gets chunk 4c+kb of key 16T+r for c = 0..3; tiled
 // tiles are lane-contiguous, row-major tiles (rows appended since the last compaction) are not.
 __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int T, int n_tiled,
@@ -74,6 +87,8 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   const int n_tiles = (l + 15) >> 4;
 
   // ---- pass 1: row max and row sum over the keys visible to each window row -----------------
+  // Only the last tiles (those reaching into the window) need the causal mask; the running sum
+  // is rescaled only when some lane's maximum moved.
   float rm[G][WT], rs[G][WT];
 #pragma unroll
   for (int h = 0; h < G; ++h)
@@ -84,6 +99,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     u32x4 kA[4];
     load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
     const int key_base = 16 * T + 4 * kb;
+    const bool full = 16 * T + 15 <= cc;                    // every row sees all 16 keys of this tile
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -95,20 +111,23 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[c]),
                                                         as_bf16x8(*(const u32x4*)(qrow + (4 * c + kb) * 16)),
                                                         acc, 0, 0, 0);
-        const int last_vis = cc + 16 * nt + r;              // row k sees keys [0, cc + k]
         float z[4];
-        float tm = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          z[e] = (key_base + e <= last_vis) ? acc[e] * scale : -INFINITY;
-          tm = fmaxf(tm, z[e]);
+        for (int e = 0; e < 4; ++e) z[e] = acc[e] * scale;
+        if (!full) {
+          const int last_vis = cc + 16 * nt + r;            // row k sees keys [0, cc + k]
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (key_base + e > last_vis) z[e] = -INFINITY;
         }
-        const float mnew = fmaxf(rm[h][nt], tm);
-        float sum = rs[h][nt] * expf(rm[h][nt] - mnew);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) sum += expf(z[e] - mnew);
-        rm[h][nt] = mnew;
-        rs[h][nt] = sum;
+        const float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+        if (__any(tm > rm[h][nt])) {
+          const float mnew = fmaxf(rm[h][nt], tm);
+          rs[h][nt] *= exp_fast(rm[h][nt] - mnew);
+          rm[h][nt] = mnew;
+        }
+        rs[h][nt] += (exp_fast(z[0] - rm[h][nt]) + exp_fast(z[1] - rm[h][nt])) +
+                     (exp_fast(z[2] - rm[h][nt]) + exp_fast(z[3] - rm[h][nt]));
       }
   }
   // merge the 4 lanes of a row, then the wavefronts
@@ -119,7 +138,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
       float m = rm[h][nt];
       m = fmaxf(m, __shfl_xor(m, 16));
       m = fmaxf(m, __shfl_xor(m, 32));
-      float s = rs[h][nt] * expf(rm[h][nt] - m);
+      float s = rs[h][nt] * exp_fast(rm[h][nt] - m);
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
       if (kb == 0) {
@@ -134,9 +153,9 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, redM[wv * ROWS + x]);
     float Z = 0.f;
 #pragma unroll
-    for (int wv = 0; wv < NW; ++wv) Z += redS[wv * ROWS + x] * expf(redM[wv * ROWS + x] - M);
+    for (int wv = 0; wv < NW; ++wv) Z += redS[wv * ROWS + x] * exp_fast(redM[wv * ROWS + x] - M);
     rowM[x] = M;
-    rowZ[x] = Z;
+    rowZ[x] = 1.f / Z;                                       // one division per row, not per logit
   }
   __syncthreads();
 #pragma unroll
@@ -170,7 +189,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           // candidates are visible to every window row; keys >= cc are discarded below
-          const float p = expf(fminf(acc[e] * scale - rm[h][nt], 0.f)) / rs[h][nt];
+          const float p = exp_fast(fminf(acc[e] * scale - rm[h][nt], 0.f)) * rs[h][nt];
           amax[e] = fmaxf(amax[e], p);
         }
       }
