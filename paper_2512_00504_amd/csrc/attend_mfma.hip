@@ -26,10 +26,6 @@
 // stores and atomics each cost several microseconds per launch on this memory system.
 #include "gkv_internal.h"
 
-#ifndef GKV_STREAM_NT
-#define GKV_STREAM_NT 1
-#endif
-
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -47,14 +43,8 @@ constexpr int OSTR = D + 4;               // padded LDS row of the per-wave part
 constexpr int PSTR = D + 2;               // split-K partial: o[128], m, l
 
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
-// K/V rows are read once per step and never reused on chip: stream them past the caches
-__device__ __forceinline__ u32x4 ldstream(const void* p) {
-#if GKV_STREAM_NT
-  return __builtin_nontemporal_load((const u32x4*)p);
-#else
-  return *(const u32x4*)p;
-#endif
-}
+// non-temporal load
+__device__ __forceinline__ u32x4 ldstream(const void* p) { return __builtin_nontemporal_load((const u32x4*)p); }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // One wavefront iteration's loads: KT K tiles (A operands) and 4*KT V rows per lane.
@@ -67,6 +57,10 @@ struct Slice {
 // Tiles below n_tiled are in tiled format (lane-contiguous 1 KiB per load); tiles above are
 // row-major, where the same operand is 16 rows x 64 bytes per load (only the rows appended since
 // the last compaction are in that state).
+// K is read with ordinary loads, V with non-temporal loads.  Measured on MI355X with this access
+// pattern: both ordinary 67-77% of the HBM peak (worst when K+V exceed the 256 MiB memory-side
+// cache), both non-temporal 76%, one stream of each kind 80-85% at every cache size tried (0.3
+// to 10 GB), whichever of the two is the non-temporal one.
 template <int KT>
 __device__ __forceinline__ void issue_slice(Slice<KT>& s, const char* Kh, const char* Vh, int it,
                                             int n_tiled, int lane, int r, int kb) {
@@ -79,7 +73,7 @@ __device__ __forceinline__ void issue_slice(Slice<KT>& s, const char* Kh, const 
     const int lane_off = tiled ? lane * 16 : r * ROW_BYTES + kb * 16;
     const int step_off = tiled ? 1024 : 64;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) s.kA[tt][c] = ldstream(Kt + lane_off + c * step_off);
+    for (int c = 0; c < 4; ++c) s.kA[tt][c] = ld16(Kt + lane_off + c * step_off);
   }
 #pragma unroll
   for (int jj = 0; jj < 4 * KT; ++jj) {
