@@ -30,14 +30,14 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 # ------------------------------------------------------------------------------------------------
 # CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
 # ------------------------------------------------------------------------------------------------
-def cpu_worker(workload: str, layer: int, seq: int, seconds: float):
+def cpu_worker(workload: str, layer: int, seq: int, seconds: float, combine: str, alpha: float):
     """Child process: run the oracle for one (layer, sequence) pair to steady state, then time
     whole compression cycles (s steps + one event) for about `seconds`."""
     from threadpoolctl import threadpool_limits
     import numpy as np  # noqa: F401
     from gkv_traces import CONFIGS, Trace
     from oracle import gkv_oracle as O
-    wl = CONFIGS[workload]
+    wl = CONFIGS[workload].with_(combine=combine, alpha=alpha)
     with threadpool_limits(limits=1):
         tr = Trace(wl)
         orc = O.OracleA(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.budget, wl.window, wl.interval,
@@ -59,7 +59,7 @@ def cpu_worker(workload: str, layer: int, seq: int, seconds: float):
     print(json.dumps({"pair_steps": done, "seconds": elapsed, "events": len(orc.events)}))
 
 
-def cpu_baseline(workload: str, seconds: float):
+def cpu_baseline(workload: str, seconds: float, combine: str, alpha: float):
     from gkv_traces import CONFIGS
     wl = CONFIGS[workload]
     n_workers = max(1, min(16, os.cpu_count() or 1, wl.n_layers * wl.batch))
@@ -67,7 +67,8 @@ def cpu_baseline(workload: str, seconds: float):
     for i in range(n_workers):
         layer, seq = (i * 7) % wl.n_layers, i % wl.batch
         procs.append(subprocess.Popen(
-            [sys.executable, os.path.abspath(__file__), "--cpu-worker", workload, str(layer), str(seq), str(seconds)],
+            [sys.executable, os.path.abspath(__file__), "--cpu-worker", workload, str(layer), str(seq), str(seconds),
+             combine, str(alpha)],
             stdout=subprocess.PIPE, text=True, cwd=ROOT))
     rate, total_steps = 0.0, 0
     for p in procs:
@@ -121,6 +122,9 @@ def main():
     ap.add_argument("--steps", type=int, default=1280)
     ap.add_argument("--warmup", type=int, default=256)
     ap.add_argument("--workload", default="cfg3_28layer_b512")
+    ap.add_argument("--combine", choices=["max", "avg", "sum"], default=None,
+                    help="global-score form (default: the workload's, max)")
+    ap.add_argument("--alpha", type=float, default=None, help="memory-decay rate (default: the workload's, 0.8)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
@@ -131,12 +135,12 @@ def main():
                     help="fill the cache prefix by repeating the first s generated steps (for the largest workloads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (for scaling rocprofv3 --pmc counters)")
-    ap.add_argument("--cpu-worker", nargs=4, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS"))
+    ap.add_argument("--cpu-worker", nargs=6, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS", "COMBINE", "ALPHA"))
     args = ap.parse_args()
 
     if args.cpu_worker:
-        wlname, layer, seq, secs = args.cpu_worker
-        cpu_worker(wlname, int(layer), int(seq), float(secs))
+        wlname, layer, seq, secs, comb, alpha = args.cpu_worker
+        cpu_worker(wlname, int(layer), int(seq), float(secs), comb, float(alpha))
         return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -144,11 +148,15 @@ def main():
 
     from gkv_traces import CONFIGS, Trace
     wl = CONFIGS[args.workload]
+    if args.combine is not None:
+        wl = wl.with_(combine=args.combine)
+    if args.alpha is not None:
+        wl = wl.with_(alpha=args.alpha)
 
     # CPU leg first, before this process touches the GPU (children are plain CPU processes)
     cpu = None
     if not args.no_cpu_baseline and not args.copy_calibration:
-        cpu = cpu_baseline(args.workload, args.cpu_seconds)
+        cpu = cpu_baseline(args.workload, args.cpu_seconds, wl.combine, wl.alpha)
 
     import torch
     from paper_2512_00504_amd.state import DecodeState

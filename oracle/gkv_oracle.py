@@ -22,7 +22,11 @@ Readings taken where the paper is silent (each is a switch or a comment here):
   * at the first compression there is no history (n_hist = 0) and the
     recorded history is the normalised score of the kept entries;
   * kept entries are stored in ascending original position, then the window;
-  * ties in the top-k: higher score first, then lower index.
+  * ties in the top-k: higher score first, then lower index;
+  * redundancy score (the paper gives no threshold, recency rule or diagonal
+    rule): see redundancy_score(); with it, selection uses lam*F - (1-lam)*R'
+    while the recorded history stays the global score F.  Parity unpinned
+    against the authors' settings; pinned here by closed forms and brute force.
 
 Pins: tests/test_oracle_pins.py (closed forms, hand-derived fixtures under
 tests/golden/, brute force, invariants).  Every function below has a pin.
@@ -141,6 +145,41 @@ def select_topk(F, k):
     return keep
 
 
+def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8):
+    """Redundancy score R [h_kv, l] of the cached keys (appendix "Integrating the Global Score
+    with Other Methods"): keys normalised to K/(||K||_2 + eps), cosine-similarity matrix C,
+    entries below the threshold tau set to zero as well as those of the most recent tokens,
+    column sums, softmax over the l columns.
+
+    Readings (the paper gives neither the threshold nor the recent-token rule): an entry is
+    kept when C >= tau; the diagonal (a key with itself) is zeroed; "most recent tokens" zeroes
+    the columns of the last n_recent rows, so those tokens collect no redundancy.
+    """
+    K = np.asarray(K, np.float64)
+    l = int(length)
+    R = np.zeros((K.shape[0], l))
+    for j in range(K.shape[0]):
+        Kj = K[j, :l]
+        Kn = Kj / (np.linalg.norm(Kj, axis=1, keepdims=True) + eps)
+        C = Kn @ Kn.T
+        Cm = np.where(C >= tau, C, 0.0)
+        np.fill_diagonal(Cm, 0.0)
+        if n_recent > 0:
+            Cm[:, l - n_recent:] = 0.0
+        col = Cm.sum(axis=0)
+        R[j] = softmax(col)
+    return R
+
+
+def combine_redundancy(F, R, lam, n_cand=None):
+    """F' = lam * F - (1 - lam) * R / max_j R over the candidates (same appendix).
+    F [h_kv, >=n_cand], R [h_kv, l]; the maximum runs over all l columns."""
+    F = np.asarray(F, np.float64); R = np.asarray(R, np.float64)
+    n_cand = F.shape[1] if n_cand is None else n_cand
+    Rn = R / R.max(axis=1, keepdims=True)
+    return lam * F[:, :n_cand] - (1.0 - lam) * Rn[:, :n_cand]
+
+
 # --------------------------------------------------------------------------
 # oracle A: compacting cache, the state machine the HIP path mirrors
 # --------------------------------------------------------------------------
@@ -149,7 +188,9 @@ class OracleA:
 
     def __init__(self, h_q, h_kv, d, budget, window, interval, capacity=None,
                  alpha=0.8, form="max", scale=None, causal_window=True,
-                 norm_over="candidates"):
+                 norm_over="candidates", redundancy=None):
+        """redundancy: None, or dict(lam=, tau=, n_recent=, eps=) to select on
+        lam*F - (1-lam)*R' (the combination the paper calls G-KV); the recorded history stays F."""
         assert h_q % h_kv == 0 and window <= interval and window < budget
         self.h_q, self.h_kv, self.d = h_q, h_kv, d
         self.b, self.w, self.s = budget, window, interval
@@ -158,6 +199,7 @@ class OracleA:
         self.alpha, self.form = alpha, form
         self.scale = 1.0 / np.sqrt(d) if scale is None else scale
         self.causal_window, self.norm_over = causal_window, norm_over
+        self.redundancy = redundancy
         self.K = np.zeros((h_kv, self.cap, d))
         self.V = np.zeros((h_kv, self.cap, d))
         self.F_hist = np.zeros((h_kv, self.cap))
@@ -200,9 +242,17 @@ class OracleA:
         l, b, w = self.len, self.b, self.w
         c = l - w
         S, F = self.score()
-        keep = select_topk(F, b - w)
-        self.events.append(dict(len=l, n_hist=self.n_hist, S=S[:, :c].copy(), F=F.copy(),
-                                keep=keep.copy()))
+        ev = dict(len=l, n_hist=self.n_hist, S=S[:, :c].copy(), F=F.copy())
+        if self.redundancy is None:
+            keep = select_topk(F, b - w)
+        else:
+            rp = self.redundancy
+            R = redundancy_score(self.K, l, rp["tau"], rp["n_recent"], rp.get("eps", 1e-8))
+            Fsel = combine_redundancy(F, R, rp["lam"], n_cand=c)
+            keep = select_topk(Fsel, b - w)
+            ev.update(R=R, Fsel=Fsel)
+        ev["keep"] = keep.copy()
+        self.events.append(ev)
         K, V, pos = self.K.copy(), self.V.copy(), self.pos.copy()
         for j in range(self.h_kv):
             kj = keep[j]

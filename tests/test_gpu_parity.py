@@ -76,6 +76,13 @@ def test_cfg3_shape_small_batch_many_layers():
     assert st["events"] == 4
 
 
+def test_cfg3_shape_32_key_slices():
+    # the other slice size of the matrix-core attend kernel
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
+    st = run_parity(wl, 768, params={"attend_tile": 32}, check_state_every_event=False)
+    assert st["events"] == 2
+
+
 def test_cfg3_full_size_sampled_units():
     # the launch configuration the benchmark times: all 896 units on the GPU, the oracle on a
     # sample of (layer, sequence) pairs that covers first/last layer and sequence

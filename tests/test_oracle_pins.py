@@ -354,3 +354,89 @@ def test_trace_generator_is_chunking_invariant_and_dtype_exact():
     np.testing.assert_array_equal(bf16_round(k), k)
     qb, kb, vb = tr.batch_steps(50, 8)
     np.testing.assert_array_equal(qb[:, 0, 0], q[:8])
+
+
+# ------------------------------------------------------------- redundancy score ----
+def test_redundancy_closed_forms():
+    l, d = 12, 16
+    eye = np.eye(l, d)[None] * 3.0                       # orthogonal keys: no similarity at all
+    R = O.redundancy_score(eye, l, tau=0.5)
+    np.testing.assert_allclose(R, 1.0 / l, rtol=1e-13)
+    # all keys identical, last m columns masked: column sums are l-1 (diagonal excluded) or 0
+    m = 3
+    same = np.tile(np.arange(1.0, d + 1)[None, None], (1, l, 1))
+    R = O.redundancy_score(same, l, tau=0.5, n_recent=m, eps=0.0)
+    den = (l - m) * np.exp(l - 1.0) + m
+    np.testing.assert_allclose(R[0, :l - m], np.exp(l - 1.0) / den, rtol=1e-12)
+    np.testing.assert_allclose(R[0, l - m:], 1.0 / den, rtol=1e-12)
+    # one duplicated key among orthogonal ones: both copies get column sum 1
+    K = np.eye(l, d)[None].copy(); K[0, 5] = 7.0 * K[0, 2]
+    R = O.redundancy_score(K, l, tau=0.5, eps=0.0)
+    den = 2 * np.e + (l - 2)
+    np.testing.assert_allclose(R[0, [2, 5]], np.e / den, rtol=1e-13)
+    np.testing.assert_allclose(np.delete(R[0], [2, 5]), 1.0 / den, rtol=1e-13)
+
+
+def test_redundancy_threshold_scale_invariance_and_hand_values():
+    # keys (1,0), (3,4)/5-direction, (0,1): cos(0,1) = 0.6, cos(1,2) = 0.8, cos(0,2) = 0
+    K = np.array([[[2.0, 0.0], [3.0, 4.0], [0.0, 5.0]]])
+    R = O.redundancy_score(K, 3, tau=0.5, eps=0.0)
+    col = np.array([0.6, 1.4, 0.8])
+    np.testing.assert_allclose(R[0], np.exp(col) / np.exp(col).sum(), rtol=1e-13)
+    R = O.redundancy_score(K, 3, tau=0.7, eps=0.0)          # 0.6 now falls below the threshold
+    col = np.array([0.0, 0.8, 0.8])
+    np.testing.assert_allclose(R[0], np.exp(col) / np.exp(col).sum(), rtol=1e-13)
+    R = O.redundancy_score(K, 3, tau=0.6, eps=0.0)          # an entry equal to the threshold is kept
+    np.testing.assert_allclose(R[0], np.exp([0.6, 1.4, 0.8]) / np.exp([0.6, 1.4, 0.8]).sum(), rtol=1e-13)
+    rng = np.random.default_rng(11)
+    K = rng.standard_normal((2, 9, 6))
+    scaled = K * rng.uniform(0.5, 4.0, size=(2, 9, 1))
+    np.testing.assert_allclose(O.redundancy_score(scaled, 9, 0.2, eps=0.0), O.redundancy_score(K, 9, 0.2, eps=0.0), rtol=1e-12)
+    R = O.redundancy_score(K, 9, 0.2, n_recent=2)
+    np.testing.assert_allclose(R.sum(axis=1), 1.0, rtol=1e-13)
+    # brute force with scalar loops
+    import math
+    for j in range(2):
+        nrm = [math.sqrt(sum(x * x for x in K[j, n])) + 1e-8 for n in range(9)]
+        col = []
+        for c in range(9):
+            tot = 0.0
+            for k in range(9):
+                cs = sum(K[j, k, i] * K[j, c, i] for i in range(6)) / (nrm[k] * nrm[c])
+                if k != c and cs >= 0.2 and c < 9 - 2:
+                    tot += cs
+            col.append(tot)
+        z = [math.exp(x) for x in col]
+        for c in range(9):
+            assert R[j, c] == pytest.approx(z[c] / sum(z), rel=1e-12)
+
+
+def test_combine_redundancy_properties():
+    rng = np.random.default_rng(12)
+    F = rng.random((2, 10)); R = rng.random((2, 14)); R /= R.sum(axis=1, keepdims=True)
+    np.testing.assert_array_equal(O.combine_redundancy(F, R, 1.0, n_cand=10), F)
+    Fp = O.combine_redundancy(F, R, 0.7, n_cand=10)
+    np.testing.assert_allclose(Fp, 0.7 * F - 0.3 * R[:, :10] / R.max(axis=1, keepdims=True), rtol=1e-14)
+    # uniform redundancy shifts every candidate equally: the selection does not change
+    U = np.full((2, 14), 1.0 / 14)
+    np.testing.assert_array_equal(O.select_topk(O.combine_redundancy(F, U, 0.7, 10), 4), O.select_topk(F, 4))
+    # a redundant copy loses against an equally scored unique token
+    F2 = np.array([[0.5, 0.5, 0.5, 0.1]]); R2 = np.array([[0.4, 0.1, 0.4, 0.1]])
+    assert O.select_topk(O.combine_redundancy(F2, R2, 0.7), 1)[0].tolist() == [1]
+
+
+def test_oracle_with_redundancy_keeps_budget_and_records_global_score():
+    cfg = SMALL
+    red = dict(lam=0.7, tau=0.3, n_recent=cfg.window)
+    orc, _, _ = _run(cfg, cfg.n_steps, O.OracleA, redundancy=red)
+    assert len(orc.events) > 5 and orc.len <= cfg.budget + cfg.interval
+    ev = orc.events[-1]
+    assert ev["keep"].shape == (cfg.n_kv_heads, cfg.budget - cfg.window)
+    # lam = 1 is plain global-score eviction
+    a, _, _ = _run(cfg, cfg.n_steps, O.OracleA, redundancy=dict(lam=1.0, tau=0.3, n_recent=0))
+    b, _, _ = _run(cfg, cfg.n_steps, O.OracleA)
+    np.testing.assert_array_equal(a.pos, b.pos)
+    # the history that is carried is the global score F, not the combined one
+    last = orc.events[-1]
+    for j in range(cfg.n_kv_heads):
+        np.testing.assert_array_equal(orc.F_hist[j, :orc.n_hist], last["F"][j, last["keep"][j]])
