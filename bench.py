@@ -125,6 +125,9 @@ def main():
     ap.add_argument("--combine", choices=["max", "avg", "sum"], default=None,
                     help="global-score form (default: the workload's, max)")
     ap.add_argument("--alpha", type=float, default=None, help="memory-decay rate (default: the workload's, 0.8)")
+    ap.add_argument("--redundancy", nargs=2, type=float, metavar=("LAMBDA", "TAU"), default=None,
+                    help="select on lambda*F - (1-lambda)*R' (redundancy score with threshold TAU, the window "
+                         "rows exempt): the paper's full G-KV; the CPU baseline leg is then skipped")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
@@ -155,7 +158,7 @@ def main():
 
     # CPU leg first, before this process touches the GPU (children are plain CPU processes)
     cpu = None
-    if not args.no_cpu_baseline and not args.copy_calibration:
+    if not args.no_cpu_baseline and not args.copy_calibration and args.redundancy is None:
         cpu = cpu_baseline(args.workload, args.cpu_seconds, wl.combine, wl.alpha)
 
     import torch
@@ -197,7 +200,8 @@ def main():
     lib = groups[0].ctx.lib
     P = lambda t: ctypes.c_void_p(t.data_ptr())
     ptrs = [dict(h=st.ctx.h, K=P(st.K), V=P(st.V), pos=P(st.pos), qwin=P(st.qwin), state=P(st.d_state),
-                 out=P(st.out), ws=P(st.workspace), Fh=P(st.F_hist), S=P(st.S), F=P(st.F), keep=P(st.keep_idx))
+                 out=P(st.out), ws=P(st.workspace), Fh=P(st.F_hist), S=P(st.S), F=P(st.F), keep=P(st.keep_idx),
+                 R=P(st.R), Fsel=P(st.F_sel))
             for st in groups]
     host = {"len": 0}
 
@@ -227,10 +231,21 @@ def main():
             if (t + 1) % s == 0 and len_host > b:
                 for g in range(NS):
                     p = ptrs[g]
-                    rc = lib.gkv_evict(p["h"], p["qwin"], p["K"], p["V"], p["Fh"], p["pos"], p["state"], t, len_host,
-                                       p["S"], p["F"], p["keep"], p["ws"], stream_of[g])
+                    if args.redundancy is None:
+                        rc = lib.gkv_evict(p["h"], p["qwin"], p["K"], p["V"], p["Fh"], p["pos"], p["state"], t, len_host,
+                                           p["S"], p["F"], p["keep"], p["ws"], stream_of[g])
+                    else:
+                        lam, tau = args.redundancy
+                        sg = stream_of[g]
+                        rc = (lib.gkv_score_window(p["h"], p["qwin"], p["K"], p["state"], t, len_host, p["S"], p["ws"], sg)
+                              or lib.gkv_global_update(p["h"], p["S"], p["Fh"], p["state"], t, len_host, p["F"], sg)
+                              or lib.gkv_redundancy_combine(p["h"], p["K"], p["state"], t, len_host, p["F"], lam, tau,
+                                                            1e-8, wl.window, p["R"], p["Fsel"], p["ws"], sg)
+                              or lib.gkv_select_topk(p["h"], p["Fsel"], p["state"], t, len_host, p["keep"], p["ws"], sg)
+                              or lib.gkv_compact(p["h"], p["keep"], p["F"], p["K"], p["V"], p["Fh"], p["pos"], p["state"],
+                                                 t, p["ws"], sg))
                     if rc:
-                        raise RuntimeError(f"gkv_evict failed: {rc}")
+                        raise RuntimeError(f"compression failed: {rc}")
                 len_host = b
         host["len"] = len_host
 
@@ -284,7 +299,7 @@ def main():
         run(chunk, t_abs + ci * s, s, one_stream)
     torch.cuda.synchronize()
     per_kernel = {}
-    for name in ("attend", "score", "global", "topk", "compact"):
+    for name in ("attend", "score", "global", "topk", "compact") + (("redundancy",) if args.redundancy else ()):
         ms = n = 0
         for st in groups:
             st.ctx.profile_enable(False)
@@ -315,6 +330,7 @@ def main():
     alg = algorithmic_bytes(wl)                       # whole batch, all layers
     att_us = per_kernel["attend"]["avg_us"]           # one launch = one group = n_layers / NS layers
     achieved = alg["attend"] / NS / (att_us * 1e-6) / 1e9
+    alg["redundancy"] = wl.n_units * ((2 if wl.dtype == "bf16" else 4) * wl.head_dim * (b + s) + 12 * (b + s))
     for name in per_kernel:
         us = per_kernel[name]["avg_us"]
         per_kernel[name]["algorithmic_MB"] = alg[name] / NS / 1e6
@@ -332,7 +348,8 @@ def main():
                    "budget": b, "window": wl.window, "interval": s, "alpha": wl.alpha,
                    "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
                    "attend_splits": args.splits, "attend_tile": args.tile, "fast_prefix": args.fast_prefix,
-                   "streams": NS, "layers_per_launch": Lg},
+                   "streams": NS, "layers_per_launch": Lg,
+                   "redundancy": args.redundancy},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),

@@ -184,6 +184,23 @@ gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, vo
                        float* F_hist, int32_t* pos, int32_t* d_state, int32_t step,
                        void* workspace, void* stream);
 
+/*
+ * Redundancy score and its combination with the global score (paper, appendix
+ * "Integrating the Global Score with Other Methods"; the paper's "G-KV" is the
+ * max-form global score with this term).  Per KV head, over the l cached keys:
+ * Kn = K/(||K||_2 + eps), C = Kn Kn^T, entries below tau are zeroed, and so are
+ * the diagonal and the columns of the n_recent newest rows (the paper gives no
+ * values for these: caller's parameters); col_j = sum_k C'_kj; R = softmax_j col;
+ * R_norm = R / max_j R; F_sel[n] = lambda*F[n] - (1-lambda)*R_norm[n] for the
+ * candidates n < l-w.  Call it between gkv_global_update and gkv_select_topk,
+ * select on F_sel, and pass F (not F_sel) to gkv_compact: the recorded history
+ * stays the global score.  R_norm, F_sel [L,B,h_kv,capacity]; F_sel must not alias F.
+ */
+gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const int32_t* d_state, int32_t step,
+                                  int32_t len_max_host, const float* F, float lambda, float tau,
+                                  float eps, int32_t n_recent, float* R_norm, float* F_sel,
+                                  void* workspace, void* stream);
+
 /* The four compression calls above in order, on caller-provided S, F, keep_idx. */
 gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
                      int32_t* d_state, int32_t step, int32_t len_max_host,
@@ -197,7 +214,7 @@ gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_
  */
 typedef enum {
   GKV_K_ATTEND = 0, GKV_K_SCORE = 1, GKV_K_GLOBAL = 2, GKV_K_TOPK = 3, GKV_K_COMPACT = 4,
-  GKV_K_COUNT = 5
+  GKV_K_REDUNDANCY = 5, GKV_K_COUNT = 6
 } gkv_kernel_id;
 gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on);
 gkv_status gkv_profile_read(gkv_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches);

@@ -145,7 +145,7 @@ def select_topk(F, k):
     return keep
 
 
-def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8):
+def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, fp32_decisions=False, return_margin=False):
     """Redundancy score R [h_kv, l] of the cached keys (appendix "Integrating the Global Score
     with Other Methods"): keys normalised to K/(||K||_2 + eps), cosine-similarity matrix C,
     entries below the threshold tau set to zero as well as those of the most recent tokens,
@@ -154,21 +154,39 @@ def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8):
     Readings (the paper gives neither the threshold nor the recent-token rule): an entry is
     kept when C >= tau; the diagonal (a key with itself) is zeroed; "most recent tokens" zeroes
     the columns of the last n_recent rows, so those tokens collect no redundancy.
+
+    The threshold turns a real number into a yes/no.  With fp32_decisions the cosine that is
+    compared and summed is formed the way an fp32 device forms it - fp32(dot) times fp32
+    reciprocal norms, fp32 products - so that both sides take that decision in the same
+    precision; everything else stays fp64.  return_margin adds, per head, the smallest
+    |C - tau| over the entries that count (how robust the decisions were).
     """
     K = np.asarray(K, np.float64)
     l = int(length)
     R = np.zeros((K.shape[0], l))
+    margin = np.full(K.shape[0], np.inf)
     for j in range(K.shape[0]):
         Kj = K[j, :l]
-        Kn = Kj / (np.linalg.norm(Kj, axis=1, keepdims=True) + eps)
-        C = Kn @ Kn.T
-        Cm = np.where(C >= tau, C, 0.0)
+        if fp32_decisions:
+            f32 = np.float32
+            ss = (Kj * Kj).sum(axis=1).astype(f32)
+            inv = f32(1.0) / (np.sqrt(ss) + f32(eps))
+            C = ((Kj @ Kj.T).astype(f32) * inv[:, None]) * inv[None, :]
+            keep = C >= f32(tau)
+            C = C.astype(np.float64)
+        else:
+            Kn = Kj / (np.linalg.norm(Kj, axis=1, keepdims=True) + eps)
+            C = Kn @ Kn.T
+            keep = C >= tau
+        Cm = np.where(keep, C, 0.0)
         np.fill_diagonal(Cm, 0.0)
         if n_recent > 0:
             Cm[:, l - n_recent:] = 0.0
         col = Cm.sum(axis=0)
         R[j] = softmax(col)
-    return R
+        off = np.abs(C - tau) + np.eye(l) * 10.0
+        margin[j] = off[:, :l - n_recent].min() if l > n_recent else np.inf
+    return (R, margin) if return_margin else R
 
 
 def combine_redundancy(F, R, lam, n_cand=None):
@@ -247,10 +265,11 @@ class OracleA:
             keep = select_topk(F, b - w)
         else:
             rp = self.redundancy
-            R = redundancy_score(self.K, l, rp["tau"], rp["n_recent"], rp.get("eps", 1e-8))
+            R, margin = redundancy_score(self.K, l, rp["tau"], rp["n_recent"], rp.get("eps", 1e-8),
+                                         fp32_decisions=rp.get("fp32_decisions", False), return_margin=True)
             Fsel = combine_redundancy(F, R, rp["lam"], n_cand=c)
             keep = select_topk(Fsel, b - w)
-            ev.update(R=R, Fsel=Fsel)
+            ev.update(R=R, Fsel=Fsel, tau_margin=margin)
         ev["keep"] = keep.copy()
         self.events.append(ev)
         K, V, pos = self.K.copy(), self.V.copy(), self.pos.copy()

@@ -17,13 +17,13 @@ LIB_PATH = os.environ.get("GKV_LIB_PATH") or os.path.join(_HERE, "libgkv.so")
 GKV_F32, GKV_BF16 = 0, 1
 GKV_COMBINE = {"max": 0, "avg": 1, "sum": 2}
 ST_LEN, ST_LEN_STEP, ST_N_HIST, ST_N_TILED = 0, 1, 2, 3     # fields of a d_state record
-KERNEL_IDS = {"attend": 0, "score": 1, "global": 2, "topk": 3, "compact": 4}
+KERNEL_IDS = {"attend": 0, "score": 1, "global": 2, "topk": 3, "compact": 4, "redundancy": 5}
 
 EXPORTS = [
     "gkv_create", "gkv_destroy", "gkv_status_string", "gkv_workspace_bytes", "gkv_workspace_init",
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
-    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read",
+    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read", "gkv_redundancy_combine",
 ]
 
 
@@ -69,6 +69,7 @@ def load_library():
     lib.gkv_select_topk.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.gkv_redundancy_combine.argtypes = [vp, vp, vp, i32, i32, vp, c_float, c_float, c_float, i32, vp, vp, vp, vp]
     lib.gkv_profile_enable.argtypes = [vp, i32]
     lib.gkv_profile_read.argtypes = [vp, i32, POINTER(c_double), POINTER(c_int64)]
     lib.gkv_profile_reset.argtypes = [vp]
@@ -167,6 +168,11 @@ class Context:
         self._check(self.lib.gkv_evict(self.h, _ptr(qwin), _ptr(K), _ptr(V), _ptr(F_hist), _ptr(pos),
                                        _ptr(d_state), step, len_max_host, _ptr(S), _ptr(F),
                                        _ptr(keep_idx), _ptr(workspace), _stream()), "gkv_evict")
+
+    def redundancy_combine(self, K, d_state, step, len_max_host, F, lam, tau, eps, n_recent, R_norm, F_sel, workspace):
+        self._check(self.lib.gkv_redundancy_combine(self.h, _ptr(K), _ptr(d_state), step, len_max_host, _ptr(F),
+                                                    lam, tau, eps, n_recent, _ptr(R_norm), _ptr(F_sel),
+                                                    _ptr(workspace), _stream()), "gkv_redundancy_combine")
 
     def profile_enable(self, on: bool):
         self._check(self.lib.gkv_profile_enable(self.h, int(on)), "gkv_profile_enable")

@@ -12,8 +12,8 @@ struct GkvProfile {
   bool on = false;
   struct Rec { hipEvent_t e0, e1; };
   std::vector<Rec> recs[GKV_K_COUNT];
-  double done_ms[GKV_K_COUNT] = {0, 0, 0, 0, 0};
-  int64_t done_n[GKV_K_COUNT] = {0, 0, 0, 0, 0};
+  double done_ms[GKV_K_COUNT] = {};
+  int64_t done_n[GKV_K_COUNT] = {};
 };
 
 void gkv_profile_events(const GkvLaunch& ln, hipEvent_t* start, hipEvent_t* stop) {
@@ -286,6 +286,22 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
   st = gkv_select_topk(ctx, F, d_state, step, len_max_host, keep_idx, workspace, stream);
   if (st != GKV_OK) return st;
   return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace, stream);
+}
+
+extern "C" gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const int32_t* d_state, int32_t step,
+                                             int32_t len_max_host, const float* F, float lambda, float tau,
+                                             float eps, int32_t n_recent, float* R_norm, float* F_sel,
+                                             void* workspace, void* stream) {
+  (void)workspace;
+  if (!ctx || !K || !d_state || !F || !R_norm || !F_sel || step < 0) return GKV_ERR_INVALID_ARG;
+  if (!(lambda >= 0.f && lambda <= 1.f) || !(tau > -1.5f && tau < 1.5f) || !(eps >= 0.f) || n_recent < 0)
+    return GKV_ERR_INVALID_ARG;
+  if (F == F_sel) return GKV_ERR_INVALID_ARG;
+  gkv_status st = check_len(ctx, len_max_host, false);
+  if (st != GKV_OK) return st;
+  GkvLaunch ln{ctx, GKV_K_REDUNDANCY, (hipStream_t)stream};
+  return hip_status(gkv_launch_redundancy(ln, ctx->dims, ctx->cfg.dtype, use_mfma_attend(ctx), K, d_state, step, F,
+                                          lambda, tau, eps, n_recent, R_norm, F_sel));
 }
 
 // ---- profiling API ------------------------------------------------------------------------------

@@ -1,0 +1,204 @@
+// Redundancy score of the cached keys and its combination with the global score
+// (paper, appendix "Integrating the Global Score with Other Methods"):
+//   Kn = K / (||K|| + eps);  C = Kn Kn^T;  entries below tau, the diagonal and the columns of
+//   the n_recent newest rows are zeroed;  col_j = sum_k C'_kj;  R = softmax_j(col);
+//   R' = R / max_j R = exp(col_j - max_j col)   (the softmax denominator cancels);
+//   F_sel = lambda * F - (1 - lambda) * R'  over the candidates.
+// One workgroup per unit.  The l x l x d contraction runs on the matrix cores for bf16, d = 128;
+// a plain vector-ALU kernel covers every other dtype / shape.
+#include "gkv_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct RedArgs {
+  const void* K; const int32_t* d_state; int32_t step; const float* F;
+  float lambda, tau, eps; int32_t n_recent; float* R_norm; float* F_sel;
+};
+
+// Column sums reach the hundreds while the decision they feed is taken at 1e-6, so they are
+// accumulated and kept in fp64 (each term is an fp32 product); the exponent cs - max is formed
+// in fp64 and only then rounded.
+__device__ __forceinline__ double block_max_f64(double v, double* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+}
+
+// Shared tail: R' from the column sums in LDS, then the combination.  cs[j] valid for j < l.
+__device__ __forceinline__ void finish_unit(const GkvDims& dm, const RedArgs& a, int unit, int l,
+                                            const double* cs, double* red) {
+  const int tid = threadIdx.x;
+  double mx = -1e300;
+  for (int j = tid; j < l; j += 256) mx = fmax(mx, cs[j]);
+  mx = block_max_f64(mx, red);
+  float* Ru = a.R_norm + (size_t)unit * dm.cap;
+  float* Fs = a.F_sel + (size_t)unit * dm.cap;
+  const float* Fu = a.F + (size_t)unit * dm.cap;
+  const int c = l - dm.w;
+  for (int j = tid; j < l; j += 256) {
+    const float rn = expf((float)(cs[j] - mx));
+    Ru[j] = rn;
+    if (j < c) Fs[j] = a.lambda * Fu[j] - (1.f - a.lambda) * rn;
+  }
+}
+
+// ---- any dtype / shape ------------------------------------------------------------------------
+// Dynamic LDS: double cs[cap]; double red[4]; float inv[cap]
+template <typename T>
+__global__ __launch_bounds__(256) void redundancy_generic_kernel(GkvDims dm, RedArgs a) {
+  extern __shared__ double smem[];
+  constexpr int EPC = Elem<T>::EPC;
+  const int tid = threadIdx.x, unit = blockIdx.x, lb = unit / dm.Hkv, d = dm.d;
+  double* cs = (double*)smem;
+  double* red = cs + dm.cap;
+  float* inv = (float*)(red + 4);
+  const SeqState st = load_state(a.d_state, lb);
+  const int l = length_before_step(st, a.step + 1, dm.cap);
+  if (l <= dm.b) return;
+  const T* Kh = (const T*)a.K + (size_t)unit * dm.cap * d;
+  for (int n = tid; n < l; n += 256) {
+    float ss = 0.f;
+    for (int ch = 0; ch < d; ++ch) {
+      const float x = Elem<T>::ld(Kh + k_elem_offset<EPC>(n, ch, d, st.n_tiled));
+      ss = fmaf(x, x, ss);
+    }
+    inv[n] = 1.f / (sqrtf(ss) + a.eps);
+  }
+  __syncthreads();
+  const int first_recent = l - a.n_recent;
+  for (int j = tid; j < l; j += 256) {
+    double col = 0.0;
+    if (j < first_recent) {
+      for (int k = 0; k < l; ++k) {
+        if (k == j) continue;
+        float dot = 0.f;
+        for (int ch = 0; ch < d; ++ch)
+          dot = fmaf(Elem<T>::ld(Kh + k_elem_offset<EPC>(k, ch, d, st.n_tiled)),
+                     Elem<T>::ld(Kh + k_elem_offset<EPC>(j, ch, d, st.n_tiled)), dot);
+        const float cv = dot * inv[k] * inv[j];
+        if (cv >= a.tau) col += (double)cv;
+      }
+    }
+    cs[j] = col;
+  }
+  __syncthreads();
+  finish_unit(dm, a, unit, l, cs, red);
+}
+
+// ---- bf16, d = 128, matrix cores ----------------------------------------------------------------
+constexpr int ROW_BYTES = 256;
+constexpr int TILE_BYTES = 16 * ROW_BYTES;
+
+__device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int T, int n_tiled,
+                                            int lane, int r, int kb) {
+  const bool tiled = 16 * T < n_tiled;
+  const char* p = Kh + (size_t)T * TILE_BYTES + (tiled ? lane * 16 : r * ROW_BYTES + kb * 16);
+  const int step_off = tiled ? 1024 : 64;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) kA[c] = *(const u32x4*)(p + c * step_off);
+}
+
+// A wavefront owns column tiles J = wave, wave+4, ...; for each it walks all row tiles T.  The
+// A operand of a tile (lane = key + 16*kblock, 8 channels) is also a valid B operand, so
+// C[k, j] = sum_c mfma(A_T[c], A_J[c]) lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
+// Dynamic LDS: double cs[cap]; double red[4]; float inv[cap]
+__global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
+  extern __shared__ double smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, kb = lane >> 4;
+  const int unit = blockIdx.x, lb = unit / dm.Hkv;
+  double* cs = (double*)smem;
+  double* red = cs + dm.cap;
+  float* inv = (float*)(red + 4);
+  const SeqState st = load_state(a.d_state, lb);
+  const int l = length_before_step(st, a.step + 1, dm.cap);
+  if (l <= dm.b) return;
+  const char* Kh = (const char*)a.K + (size_t)unit * dm.cap * ROW_BYTES;
+  const int n_tiles = (l + 15) >> 4;
+
+  // row norms: a quarter-wave per row, 16 bytes per lane
+  for (int n = tid >> 4; n < n_tiles * 16; n += 16) {
+    float ss = 0.f;
+    if (n < l) {
+      const int ch = tid & 15;
+      const char* p = (n < st.n_tiled) ? Kh + (size_t)(n >> 4) * TILE_BYTES + ch * 256 + (n & 15) * 16
+                                       : Kh + (size_t)n * ROW_BYTES + ch * 16;
+      const u32x4 v = *(const u32x4*)p;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xffff0000u);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    }
+    ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4); ss += __shfl_xor(ss, 8);
+    if ((tid & 15) == 0) inv[n] = n < l ? 1.f / (sqrtf(ss) + a.eps) : 0.f;
+  }
+  __syncthreads();
+
+  // NC column tiles per wavefront pass, so that each row tile fetched (from L2) is used NC times
+  constexpr int NC = 4;
+  const int first_recent = l - a.n_recent;
+  for (int J0 = wave * NC; J0 < n_tiles; J0 += 4 * NC) {
+    u32x4 colA[NC][4];
+    float inv_j[NC];
+    double col[NC];
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) {
+      const int J = min(J0 + cc, n_tiles - 1);            // a clamped duplicate is computed and dropped
+      load_k_tile(colA[cc], Kh, J, st.n_tiled, lane, r, kb);
+      inv_j[cc] = inv[16 * J + r];
+      col[cc] = 0.0;
+    }
+    for (int T = 0; T < n_tiles; ++T) {
+      u32x4 rowA[4];
+      load_k_tile(rowA, Kh, T, st.n_tiled, lane, r, kb);
+      const int k0 = 16 * T + 4 * kb;
+      const f32x4 invk = *(const f32x4*)(inv + k0);      // rows >= l have inv = 0
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rowA[c]),
+                                                        __builtin_bit_cast(bf16x8, colA[cc][c]), acc, 0, 0, 0);
+        const int j = 16 * (J0 + cc) + r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float cv = acc[e] * invk[e] * inv_j[cc];
+          if (cv >= a.tau && k0 + e != j && k0 + e < l) col[cc] += (double)cv;
+        }
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) {
+      double v = col[cc];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      const int j = 16 * (J0 + cc) + r;
+      if (kb == 0 && J0 + cc < n_tiles && j < l) cs[j] = j < first_recent ? v : 0.0;
+    }
+  }
+  __syncthreads();
+  finish_unit(dm, a, unit, l, cs, red);
+}
+
+}  // namespace
+
+hipError_t gkv_launch_redundancy(const GkvLaunch& ln, const GkvDims& dm, int dtype, bool mfma, const void* K,
+                                 const int32_t* d_state, int32_t step, const float* F, float lambda, float tau,
+                                 float eps, int32_t n_recent, float* R_norm, float* F_sel) {
+  RedArgs a{K, d_state, step, F, lambda, tau, eps, n_recent, R_norm, F_sel};
+  const int units = dm.L * dm.B * dm.Hkv;
+  const size_t shmem = sizeof(double) * ((size_t)dm.cap + 4) + sizeof(float) * (size_t)dm.cap;
+  if (mfma) return gkv_launch(ln, redundancy_mfma_kernel, dim3(units), dim3(256), shmem, dm, a);
+  if (dtype == GKV_F32)
+    return gkv_launch(ln, redundancy_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);
+  return gkv_launch(ln, redundancy_generic_kernel<uint16_t>, dim3(units), dim3(256), shmem, dm, a);
+}

@@ -60,6 +60,8 @@ class DecodeState:
         self.F_hist = z(L, B, Hkv, cap, dtype=torch.float32)
         self.S = z(L, B, Hkv, cap, dtype=torch.float32)
         self.F = z(L, B, Hkv, cap, dtype=torch.float32)
+        self.R = z(L, B, Hkv, cap, dtype=torch.float32)      # normalised redundancy score
+        self.F_sel = z(L, B, Hkv, cap, dtype=torch.float32)  # lambda*F - (1-lambda)*R'
         self.keep_idx = z(L, B, Hkv, b - w, dtype=torch.int32)
         self.out = z(L, B, Hq, d, dtype=dt)
         self.workspace = torch.zeros(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
@@ -115,8 +117,13 @@ class DecodeState:
     def global_update(self, step):
         self.ctx.global_update(self.S, self.F_hist, self.d_state, step, self.len_host, self.F)
 
-    def select_topk(self, step):
-        self.ctx.select_topk(self.F, self.d_state, step, self.len_host, self.keep_idx, self.workspace)
+    def redundancy_combine(self, step, lam, tau, n_recent, eps=1e-8):
+        self.ctx.redundancy_combine(self.K, self.d_state, step, self.len_host, self.F, lam, tau, eps, n_recent,
+                                    self.R, self.F_sel, self.workspace)
+
+    def select_topk(self, step, on_combined=False):
+        self.ctx.select_topk(self.F_sel if on_combined else self.F, self.d_state, step, self.len_host,
+                             self.keep_idx, self.workspace)
 
     def compact(self, step):
         self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_state, step,

@@ -46,7 +46,7 @@ def check_scores(s_gpu, s_ref, what=""):
                            f"{(err / (np.abs(s_ref) + 1e-300)).max():.3e}")
 
 
-def check_keep(keep_gpu, keep_ref, F_ref, what=""):
+def check_keep(keep_gpu, keep_ref, F_ref, what="", abs_tol=None):
     """Kept index sets must be identical, except swaps between candidates whose oracle scores
     differ by less than SWAP_REL relative (or are both below SWAP_TINY).  Returns #swapped."""
     keep_gpu = np.asarray(keep_gpu, np.int64)
@@ -59,7 +59,10 @@ def check_keep(keep_gpu, keep_ref, F_ref, what=""):
     only_ref = np.setdiff1d(keep_ref, keep_gpu)
     vals = np.concatenate([F_ref[only_gpu], F_ref[only_ref]])
     hi, lo = vals.max(), vals.min()
-    ok = (hi - lo) <= SWAP_REL * hi or hi < SWAP_TINY
+    if abs_tol is not None:
+        ok = (hi - lo) <= abs_tol
+    else:
+        ok = (hi - lo) <= SWAP_REL * hi or hi < SWAP_TINY
     assert ok, (f"{what}: kept sets differ beyond tolerance: gpu-only {only_gpu.tolist()} "
                 f"ref-only {only_ref.tolist()} scores {vals.tolist()}")
     return len(only_gpu)
@@ -78,18 +81,24 @@ def upload_oracle_state(st: DecodeState, orc, l, b, next_step):
     st.d_state[l, b] = torch.tensor([orc.len, next_step, orc.n_hist, n_tiled], dtype=torch.int32)
 
 
+RED_MARGIN = 4e-7        # the oracle thresholds an fp32 cosine like the kernel's; closer than this may still differ
+RED_SWAP_ABS = 2e-6      # combined scores are O(1) and can be negative: absolute swap tolerance
+
+
 def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_every_event=True,
-               cfg_over=None, fused_evict=False):
+               cfg_over=None, fused_evict=False, redundancy=None):
     """Run GPU (all units) and oracle (the (layer, seq) `pairs`, default all) side by side.
     Returns a dict of statistics.  Asserts parity at every step and event."""
     tr = Trace(wl)
     st = DecodeState.from_workload(wl, params=params, **(cfg_over or {}))
     if pairs is None:
         pairs = [(l, b) for l in range(wl.n_layers) for b in range(wl.batch)]
-    orcs = {p: make_oracle(wl) for p in pairs}
+    if redundancy is not None:
+        redundancy = dict(redundancy, fp32_decisions=True)
+    orcs = {p: make_oracle(wl, redundancy=redundancy) for p in pairs}
     dt = TORCH_DT[wl.dtype]
     dev = st.device
-    stats = dict(events=0, swaps=0, max_out_err=0.0, steps=n_steps)
+    stats = dict(events=0, swaps=0, max_out_err=0.0, steps=n_steps, ambiguous=0)
     hkv = wl.n_kv_heads
     for t0 in range(0, n_steps, chunk):
         n = min(chunk, n_steps - t0)
@@ -104,11 +113,17 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
             outs.append(out.clone())
             ev_gpu = None
             if st.is_trigger(t):
-                if fused_evict:
+                if redundancy is not None:
+                    st.score_window(t); st.global_update(t)
+                    st.redundancy_combine(t, redundancy["lam"], redundancy["tau"], redundancy["n_recent"],
+                                          redundancy.get("eps", 1e-8))
+                    st.select_topk(t, on_combined=True); st.compact(t)
+                elif fused_evict:
                     st.evict(t)
                 else:
                     st.score_window(t); st.global_update(t); st.select_topk(t); st.compact(t)
-                ev_gpu = dict(S=st.S.cpu().numpy(), F=st.F.cpu().numpy(), keep=st.keep_idx.cpu().numpy())
+                ev_gpu = dict(S=st.S.cpu().numpy(), F=st.F.cpu().numpy(), keep=st.keep_idx.cpu().numpy(),
+                              R=st.R.cpu().numpy(), Fsel=st.F_sel.cpu().numpy())
             for (l, b), orc in orcs.items():
                 n_ev = len(orc.events)
                 ref = orc.step(t, q[i, l, b], k[i, l, b], v[i, l, b])
@@ -126,7 +141,19 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                         what = f"t={t} pair=({l},{b}) head={j}"
                         check_scores(ev_gpu["S"][l, b, j, :c], ev["S"][j], "S " + what)
                         check_scores(ev_gpu["F"][l, b, j, :c], ev["F"][j], "F " + what)
-                        swapped += check_keep(ev_gpu["keep"][l, b, j], ev["keep"][j], ev["F"][j], "keep " + what)
+                        if redundancy is None:
+                            swapped += check_keep(ev_gpu["keep"][l, b, j], ev["keep"][j], ev["F"][j], "keep " + what)
+                        elif ev["tau_margin"][j] < RED_MARGIN:
+                            stats["ambiguous"] += 1              # threshold decision not robust: skip, resync
+                            swapped += 1
+                        else:
+                            Rn = ev["R"][j] / ev["R"][j].max()
+                            np.testing.assert_allclose(ev_gpu["R"][l, b, j, :ev["len"]], Rn, rtol=2e-5, atol=1e-30,
+                                                       err_msg="R " + what)
+                            np.testing.assert_allclose(ev_gpu["Fsel"][l, b, j, :c], ev["Fsel"][j], rtol=0, atol=1e-5,
+                                                       err_msg="Fsel " + what)
+                            swapped += check_keep(ev_gpu["keep"][l, b, j], ev["keep"][j], ev["Fsel"][j],
+                                                  "keep " + what, abs_tol=RED_SWAP_ABS)
                     stats["swaps"] += swapped
                     if swapped:
                         upload_oracle_state(st, orc, l, b, t + 1)

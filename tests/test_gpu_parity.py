@@ -119,6 +119,52 @@ def test_cfg5_shape_heavy_tailed_keys():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+# ------------------------------------------------------------------ redundancy score (full G-KV)
+def test_redundancy_cfg1_generic_fp32():
+    wl = CONFIGS["cfg1_tiny"]
+    st = run_parity(wl, 160, redundancy=dict(lam=0.7, tau=0.1, n_recent=wl.window))
+    assert st["events"] == 6
+    _say(f"  ambiguous thresholds {st['ambiguous']} swaps {st['swaps']}")
+
+
+def test_redundancy_cfg3_shape_matrix_cores():
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
+    st = run_parity(wl, 1024, redundancy=dict(lam=0.7, tau=0.5, n_recent=wl.window), check_state_every_event=False)
+    assert st["events"] == 4
+    _say(f"  ambiguous thresholds {st['ambiguous']} swaps {st['swaps']}")
+
+
+def test_redundancy_cfg5_shape_and_lambda_one():
+    wl = CONFIGS["cfg5_large_batch"].with_(n_layers=1, batch=1)
+    st = run_parity(wl, 1152, redundancy=dict(lam=0.9, tau=0.4, n_recent=0), check_state_every_event=False)
+    assert st["events"] == 2
+    # lambda = 1 must reproduce plain global-score eviction bit for bit
+    wl2 = CONFIGS["cfg2_single_layer"]
+    a = run_parity(wl2, 768, redundancy=dict(lam=1.0, tau=0.5, n_recent=0), check_state_every_event=False)
+    b = run_parity(wl2, 768, check_state_every_event=False)
+    n = wl2.budget
+    assert torch.equal(a["state"].pos[..., :n], b["state"].pos[..., :n])
+    assert torch.equal(a["state"].V[..., :n, :], b["state"].V[..., :n, :])
+
+
+def test_redundancy_closed_form_duplicate_keys():
+    # orthogonal keys with one duplicated pair: R' = 1 for the pair, exp(-1) for everyone else
+    st = _state("bf16", head_dim=128, n_q_heads=2, n_kv_heads=2, budget=32, window=4, interval=8, capacity=64)
+    l = 40
+    K = torch.zeros(1, 2, 2, 64, 128)
+    for n in range(l):
+        K[..., n, n] = 2.0
+    K[..., 9, :] = 0; K[..., 9, 3] = 5.0                    # row 9 duplicates the direction of row 3
+    st.K.copy_(K.to(torch.bfloat16)); st.F.fill_(0.5)
+    _set_lengths(st, (l, l), step_next=l)
+    st.redundancy_combine(l - 1, lam=0.7, tau=0.5, n_recent=0, eps=0.0)
+    R = st.R[0, 0, 0, :l].double().cpu().numpy()
+    expect = np.full(l, np.exp(-1.0)); expect[[3, 9]] = 1.0
+    np.testing.assert_allclose(R, expect, rtol=1e-6)
+    Fs = st.F_sel[0, 1, 1, :l - 4].double().cpu().numpy()
+    np.testing.assert_allclose(Fs, 0.7 * 0.5 - 0.3 * expect[:l - 4], rtol=1e-6)
+
+
 # ------------------------------------------------------------------ single calls, edge cases
 def _state(dtype="f32", **kw):
     base = dict(n_layers=1, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, budget=32, window=4,

@@ -411,6 +411,15 @@ def test_redundancy_threshold_scale_invariance_and_hand_values():
             assert R[j, c] == pytest.approx(z[c] / sum(z), rel=1e-12)
 
 
+def test_redundancy_fp32_decisions_agree_away_from_the_threshold():
+    rng = np.random.default_rng(13)
+    K = rng.standard_normal((2, 40, 16)).astype(np.float32).astype(np.float64)
+    R64, m = O.redundancy_score(K, 40, 0.3, n_recent=4, return_margin=True)
+    R32 = O.redundancy_score(K, 40, 0.3, n_recent=4, fp32_decisions=True)
+    assert (m > 1e-5).all()                      # no entry near tau in this draw, so decisions agree
+    np.testing.assert_allclose(R32, R64, rtol=1e-5)
+
+
 def test_combine_redundancy_properties():
     rng = np.random.default_rng(12)
     F = rng.random((2, 10)); R = rng.random((2, 14)); R /= R.sum(axis=1, keepdims=True)
