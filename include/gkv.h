@@ -201,6 +201,17 @@ gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const int32_t* d_
                                   float eps, int32_t n_recent, float* R_norm, float* F_sel,
                                   void* workspace, void* stream);
 
+/*
+ * Eviction log (paper, Section 5: the positions of the tokens actually evicted during
+ * generation are recorded and later build the sparse attention mask).  Call after
+ * gkv_select_topk and BEFORE gkv_compact: writes, per unit, the original positions
+ * (pos values) of the candidates that are not in keep_idx, ascending, padded with -1
+ * to `interval` entries.  evicted [L,B,h_kv,interval].  Sequences not above the budget
+ * get all -1.
+ */
+gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const int32_t* pos,
+                                 const int32_t* d_state, int32_t step, int32_t* evicted, void* stream);
+
 /* The four compression calls above in order, on caller-provided S, F, keep_idx. */
 gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
                      int32_t* d_state, int32_t step, int32_t len_max_host,

@@ -271,6 +271,9 @@ class OracleA:
             keep = select_topk(Fsel, b - w)
             ev.update(R=R, Fsel=Fsel, tau_margin=margin)
         ev["keep"] = keep.copy()
+        # eviction log: original positions of the candidates that are dropped (Section 5)
+        ev["evicted_pos"] = [sorted(set(self.pos[j, :c].tolist()) - set(self.pos[j, keep[j]].tolist()))
+                             for j in range(self.h_kv)]
         self.events.append(ev)
         K, V, pos = self.K.copy(), self.V.copy(), self.pos.copy()
         for j in range(self.h_kv):

@@ -207,6 +207,43 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   }
 }
 
+// ---- eviction log: original positions of the candidates that are about to be dropped -------
+// Dynamic LDS: uint32 kept[cap]
+__global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, const int32_t* __restrict__ keep_idx,
+                                                                const int32_t* __restrict__ pos,
+                                                                const int32_t* __restrict__ d_state, int step,
+                                                                int32_t* __restrict__ evicted) {
+  extern __shared__ uint32_t kept[];
+  __shared__ int tmp[4];
+  const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
+  int32_t* Eu = evicted + (size_t)unit * dm.s;
+  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
+  if (l <= dm.b) {
+    for (int i = tid; i < dm.s; i += 256) Eu[i] = -1;
+    return;
+  }
+  const int c = l - dm.w, k = dm.b - dm.w;
+  for (int n = tid; n < c; n += 256) kept[n] = 0u;
+  __syncthreads();
+  const int32_t* Ku = keep_idx + (size_t)unit * k;
+  for (int r = tid; r < k; r += 256) {
+    const int n = Ku[r];
+    if (n >= 0 && n < c) kept[n] = 1u;
+  }
+  __syncthreads();
+  const int per = (c + 255) / 256;
+  const int lo = tid * per, hi = min(c, lo + per);
+  int n_out = 0;
+  for (int n = lo; n < hi; ++n) n_out += (kept[n] == 0u);
+  int out = block_inclusive_scan(n_out, tmp) - n_out;
+  const int32_t* pu = pos + (size_t)unit * dm.cap;
+  for (int n = lo; n < hi; ++n)
+    if (kept[n] == 0u && out < dm.s) Eu[out++] = pu[n];
+  // pad what is left (a full cache evicts exactly l - b <= s rows)
+  const int total = c - k;
+  for (int i = total + tid; i < dm.s; i += 256) Eu[i] = -1;
+}
+
 __global__ void finalize_state_kernel(GkvDims dm, int32_t* d_state, int step) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= dm.L * dm.B) return;
@@ -245,6 +282,13 @@ hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, c
   const int nlb = dm.L * dm.B;
   GkvLaunch plain{ln.ctx, -1, ln.stream};
   return gkv_launch(plain, finalize_state_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_state, (int)step);
+}
+
+hipError_t gkv_launch_evicted_positions(const GkvLaunch& ln, const GkvDims& dm, const int32_t* keep_idx,
+                                        const int32_t* pos, const int32_t* d_state, int32_t step, int32_t* evicted) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, evicted_positions_kernel, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, keep_idx, pos,
+                    d_state, (int)step, evicted);
 }
 
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n) {

@@ -304,6 +304,13 @@ extern "C" gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const 
                                           lambda, tau, eps, n_recent, R_norm, F_sel));
 }
 
+extern "C" gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const int32_t* pos,
+                                            const int32_t* d_state, int32_t step, int32_t* evicted, void* stream) {
+  if (!ctx || !keep_idx || !pos || !d_state || !evicted || step < 0) return GKV_ERR_INVALID_ARG;
+  GkvLaunch ln{ctx, -1, (hipStream_t)stream};
+  return hip_status(gkv_launch_evicted_positions(ln, ctx->dims, keep_idx, pos, d_state, step, evicted));
+}
+
 // ---- profiling API ------------------------------------------------------------------------------
 extern "C" gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on) {
   if (!ctx || !ctx->prof) return GKV_ERR_INVALID_ARG;

@@ -63,6 +63,7 @@ class DecodeState:
         self.R = z(L, B, Hkv, cap, dtype=torch.float32)      # normalised redundancy score
         self.F_sel = z(L, B, Hkv, cap, dtype=torch.float32)  # lambda*F - (1-lambda)*R'
         self.keep_idx = z(L, B, Hkv, b - w, dtype=torch.int32)
+        self.evicted = torch.full((L, B, Hkv, cfg.interval), -1, dtype=torch.int32, device=dev)
         self.out = z(L, B, Hq, d, dtype=dt)
         self.workspace = torch.zeros(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
         self.ctx.workspace_init(self.workspace)
@@ -124,6 +125,10 @@ class DecodeState:
     def select_topk(self, step, on_combined=False):
         self.ctx.select_topk(self.F_sel if on_combined else self.F, self.d_state, step, self.len_host,
                              self.keep_idx, self.workspace)
+
+    def evicted_positions(self, step):
+        """Eviction log of this compression; call between select_topk and compact."""
+        self.ctx.evicted_positions(self.keep_idx, self.pos, self.d_state, step, self.evicted)
 
     def compact(self, step):
         self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_state, step,

@@ -121,9 +121,11 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                 elif fused_evict:
                     st.evict(t)
                 else:
-                    st.score_window(t); st.global_update(t); st.select_topk(t); st.compact(t)
+                    st.score_window(t); st.global_update(t); st.select_topk(t)
+                    st.evicted_positions(t); st.compact(t)
                 ev_gpu = dict(S=st.S.cpu().numpy(), F=st.F.cpu().numpy(), keep=st.keep_idx.cpu().numpy(),
-                              R=st.R.cpu().numpy(), Fsel=st.F_sel.cpu().numpy())
+                              R=st.R.cpu().numpy(), Fsel=st.F_sel.cpu().numpy(),
+                              evicted=st.evicted.cpu().numpy())
             for (l, b), orc in orcs.items():
                 n_ev = len(orc.events)
                 ref = orc.step(t, q[i, l, b], k[i, l, b], v[i, l, b])
@@ -154,6 +156,12 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                                                        err_msg="Fsel " + what)
                             swapped += check_keep(ev_gpu["keep"][l, b, j], ev["keep"][j], ev["Fsel"][j],
                                                   "keep " + what, abs_tol=RED_SWAP_ABS)
+                    if not swapped and redundancy is None and not fused_evict:
+                        for j in range(hkv):                 # eviction log: bit-exact when the kept sets agree
+                            log = ev_gpu["evicted"][l, b, j]
+                            n_ev_rows = len(ev["evicted_pos"][j])
+                            assert log[:n_ev_rows].tolist() == ev["evicted_pos"][j], f"eviction log t={t} ({l},{b},{j})"
+                            assert (log[n_ev_rows:] == -1).all()
                     stats["swaps"] += swapped
                     if swapped:
                         upload_oracle_state(st, orc, l, b, t + 1)

@@ -286,6 +286,24 @@ def test_compacting_oracle_equals_mask_oracle(form):
         np.testing.assert_allclose(a.F_hist[j, :a.n_hist], [b.hist[j][n] for n in alive[:a.n_hist]], rtol=1e-12)
 
 
+def test_eviction_log_matches_the_mask_oracle():
+    # what oracle A logs as evicted is exactly what leaves oracle B's alive set at each event
+    a, _, _ = _run(SMALL, SMALL.n_steps, O.OracleA)
+    tr = Trace(SMALL)
+    q, k, v = tr.unit_steps(0, 0, 0, SMALL.n_steps)
+    b = O.OracleB(SMALL.n_q_heads, SMALL.n_kv_heads, SMALL.head_dim, SMALL.budget, SMALL.window, SMALL.interval)
+    n_ev = 0
+    for t in range(SMALL.n_steps):
+        before = [set(x) | {t} for x in b.alive]
+        b.step(t, q[t], k[t], v[t])
+        if len(b.kept_log) > n_ev:
+            for j in range(SMALL.n_kv_heads):
+                assert sorted(before[j] - b.alive[j]) == a.events[n_ev]["evicted_pos"][j]
+                assert len(a.events[n_ev]["evicted_pos"][j]) == a.events[n_ev]["len"] - SMALL.budget
+            n_ev += 1
+    assert n_ev == len(a.events) > 5
+
+
 def test_compacted_attention_equals_masked_dense_attention_over_history():
     cfg = SMALL
     orc, outs, (q, k, v) = _run(cfg, 41)
