@@ -202,6 +202,15 @@ gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const int32_t* d_
                                   void* workspace, void* stream);
 
 /*
+ * SnapKV-style plug-in (paper, same appendix): sequence-wise max-pooling of a score over
+ * the candidates, F_out[n] = max F[m] for |m - n| <= kernel/2, clipped at the ends.  The
+ * paper gives no kernel size (caller's parameter).  Select on F_out, record F.
+ * F_out must not alias F.  F, F_out [L,B,h_kv,capacity].
+ */
+gkv_status gkv_pool_scores(gkv_ctx* ctx, const float* F, const int32_t* d_state, int32_t step,
+                           int32_t kernel, float* F_out, void* stream);
+
+/*
  * Eviction log (paper, Section 5: the positions of the tokens actually evicted during
  * generation are recorded and later build the sparse attention mask).  Call after
  * gkv_select_topk and BEFORE gkv_compact: writes, per unit, the original positions

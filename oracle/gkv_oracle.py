@@ -145,6 +145,19 @@ def select_topk(F, k):
     return keep
 
 
+def pool_scores(F, kernel):
+    """Sequence-wise max-pooling of a score over the candidates, the SnapKV-style plug-in the
+    appendix applies to the global score: out[n] = max F[m] for |m - n| <= kernel // 2, clipped at
+    the ends.  The paper does not give the kernel size (parameter; odd sizes are symmetric)."""
+    F = np.asarray(F, np.float64)
+    h, c = F.shape
+    half = kernel // 2
+    out = np.empty_like(F)
+    for n in range(c):
+        out[:, n] = F[:, max(0, n - half):min(c, n + half + 1)].max(axis=1)
+    return out
+
+
 def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, fp32_decisions=False, return_margin=False):
     """Redundancy score R [h_kv, l] of the cached keys (appendix "Integrating the Global Score
     with Other Methods"): keys normalised to K/(||K||_2 + eps), cosine-similarity matrix C,

@@ -23,7 +23,7 @@ EXPORTS = [
     "gkv_create", "gkv_destroy", "gkv_status_string", "gkv_workspace_bytes", "gkv_workspace_init",
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
-    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read", "gkv_redundancy_combine", "gkv_evicted_positions",
+    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read", "gkv_redundancy_combine", "gkv_evicted_positions", "gkv_pool_scores",
 ]
 
 
@@ -70,6 +70,7 @@ def load_library():
     lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.gkv_redundancy_combine.argtypes = [vp, vp, vp, i32, i32, vp, c_float, c_float, c_float, i32, vp, vp, vp, vp]
+    lib.gkv_pool_scores.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.gkv_evicted_positions.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     lib.gkv_profile_enable.argtypes = [vp, i32]
     lib.gkv_profile_read.argtypes = [vp, i32, POINTER(c_double), POINTER(c_int64)]
@@ -174,6 +175,10 @@ class Context:
         self._check(self.lib.gkv_redundancy_combine(self.h, _ptr(K), _ptr(d_state), step, len_max_host, _ptr(F),
                                                     lam, tau, eps, n_recent, _ptr(R_norm), _ptr(F_sel),
                                                     _ptr(workspace), _stream()), "gkv_redundancy_combine")
+
+    def pool_scores(self, F, d_state, step, kernel, F_out):
+        self._check(self.lib.gkv_pool_scores(self.h, _ptr(F), _ptr(d_state), step, kernel, _ptr(F_out), _stream()),
+                    "gkv_pool_scores")
 
     def evicted_positions(self, keep_idx, pos, d_state, step, evicted):
         self._check(self.lib.gkv_evicted_positions(self.h, _ptr(keep_idx), _ptr(pos), _ptr(d_state), step,

@@ -207,6 +207,28 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   }
 }
 
+// ---- sequence-wise max-pooling of a score over the candidates --------------------------------
+// Dynamic LDS: float f[cap]
+__global__ __launch_bounds__(256) void pool_scores_kernel(GkvDims dm, const float* __restrict__ F,
+                                                          const int32_t* __restrict__ d_state, int step,
+                                                          int kernel, float* __restrict__ F_out) {
+  extern __shared__ float fbuf[];
+  const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
+  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
+  if (l <= dm.b) return;
+  const int c = l - dm.w, half = kernel / 2;
+  const float* Fu = F + (size_t)unit * dm.cap;
+  for (int n = tid; n < c; n += 256) fbuf[n] = Fu[n];
+  __syncthreads();
+  float* Fo = F_out + (size_t)unit * dm.cap;
+  for (int n = tid; n < c; n += 256) {
+    const int lo = max(0, n - half), hi = min(c - 1, n + half);
+    float m = fbuf[lo];
+    for (int x = lo + 1; x <= hi; ++x) m = fmaxf(m, fbuf[x]);
+    Fo[n] = m;
+  }
+}
+
 // ---- eviction log: original positions of the candidates that are about to be dropped -------
 // Dynamic LDS: uint32 kept[cap]
 __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, const int32_t* __restrict__ keep_idx,
@@ -282,6 +304,13 @@ hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, c
   const int nlb = dm.L * dm.B;
   GkvLaunch plain{ln.ctx, -1, ln.stream};
   return gkv_launch(plain, finalize_state_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_state, (int)step);
+}
+
+hipError_t gkv_launch_pool_scores(const GkvLaunch& ln, const GkvDims& dm, const float* F, const int32_t* d_state,
+                                  int32_t step, int32_t kernel, float* F_out) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, pool_scores_kernel, dim3(units), dim3(256), sizeof(float) * dm.cap, dm, F, d_state, (int)step,
+                    (int)kernel, F_out);
 }
 
 hipError_t gkv_launch_evicted_positions(const GkvLaunch& ln, const GkvDims& dm, const int32_t* keep_idx,

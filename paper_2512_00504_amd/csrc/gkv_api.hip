@@ -304,6 +304,13 @@ extern "C" gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const 
                                           lambda, tau, eps, n_recent, R_norm, F_sel));
 }
 
+extern "C" gkv_status gkv_pool_scores(gkv_ctx* ctx, const float* F, const int32_t* d_state, int32_t step,
+                                      int32_t kernel, float* F_out, void* stream) {
+  if (!ctx || !F || !d_state || !F_out || step < 0 || kernel < 1 || F == F_out) return GKV_ERR_INVALID_ARG;
+  GkvLaunch ln{ctx, -1, (hipStream_t)stream};
+  return hip_status(gkv_launch_pool_scores(ln, ctx->dims, F, d_state, step, kernel, F_out));
+}
+
 extern "C" gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const int32_t* pos,
                                             const int32_t* d_state, int32_t step, int32_t* evicted, void* stream) {
   if (!ctx || !keep_idx || !pos || !d_state || !evicted || step < 0) return GKV_ERR_INVALID_ARG;

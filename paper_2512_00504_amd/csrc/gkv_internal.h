@@ -74,6 +74,8 @@ hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, c
 hipError_t gkv_launch_redundancy(const GkvLaunch& ln, const GkvDims& dm, int dtype, bool mfma, const void* K,
                                  const int32_t* d_state, int32_t step, const float* F, float lambda, float tau,
                                  float eps, int32_t n_recent, float* R_norm, float* F_sel);
+hipError_t gkv_launch_pool_scores(const GkvLaunch& ln, const GkvDims& dm, const float* F, const int32_t* d_state,
+                                  int32_t step, int32_t kernel, float* F_out);
 hipError_t gkv_launch_evicted_positions(const GkvLaunch& ln, const GkvDims& dm, const int32_t* keep_idx,
                                         const int32_t* pos, const int32_t* d_state, int32_t step, int32_t* evicted);
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n);

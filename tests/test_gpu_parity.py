@@ -165,6 +165,22 @@ def test_redundancy_closed_form_duplicate_keys():
     np.testing.assert_allclose(Fs, 0.7 * 0.5 - 0.3 * expect[:l - 4], rtol=1e-6)
 
 
+def test_pool_scores_against_oracle():
+    st = _state()
+    l, w = 45, 4
+    c = l - w
+    F = torch.rand(1, 2, 2, 64)
+    st.F.copy_(F)
+    _set_lengths(st, (l, 20), step_next=l)                      # sequence 1 is below the budget: untouched
+    st.F_sel.fill_(-7.0)
+    for kernel in (1, 5, 8, 200):
+        st.ctx.pool_scores(st.F, st.d_state, l - 1, kernel, st.F_sel)
+        got = st.F_sel.cpu().numpy()
+        ref = O.pool_scores(F[0, 0, :, :c].double().numpy(), kernel)
+        np.testing.assert_array_equal(got[0, 0, :, :c].astype(np.float64), ref)
+        assert (got[0, 1] == -7.0).all()
+
+
 # ------------------------------------------------------------------ single calls, edge cases
 def _state(dtype="f32", **kw):
     base = dict(n_layers=1, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, budget=32, window=4,

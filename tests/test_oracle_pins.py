@@ -467,3 +467,18 @@ def test_oracle_with_redundancy_keeps_budget_and_records_global_score():
     last = orc.events[-1]
     for j in range(cfg.n_kv_heads):
         np.testing.assert_array_equal(orc.F_hist[j, :orc.n_hist], last["F"][j, last["keep"][j]])
+
+
+def test_pool_scores():
+    rng = np.random.default_rng(14)
+    F = rng.random((2, 17))
+    np.testing.assert_array_equal(O.pool_scores(F, 1), F)
+    spike = np.zeros((1, 11)); spike[0, 4] = 1.0
+    assert O.pool_scores(spike, 5)[0].tolist() == [0, 0, 1, 1, 1, 1, 1, 0, 0, 0, 0]
+    assert O.pool_scores(spike, 3)[0].tolist() == [0, 0, 0, 1, 1, 1, 0, 0, 0, 0, 0]
+    P7 = O.pool_scores(F, 7)
+    assert (P7 >= F).all()
+    for j in range(2):
+        for n in range(17):
+            assert P7[j, n] == max(F[j, m] for m in range(17) if abs(m - n) <= 3)
+    np.testing.assert_array_equal(O.pool_scores(F, 99), np.broadcast_to(F.max(axis=1, keepdims=True), F.shape))
