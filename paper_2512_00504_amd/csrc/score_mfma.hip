@@ -11,6 +11,10 @@
 //           (Eq. 2).  Only S leaves the chip; the [g, w, l] matrix never exists in memory.
 #include "gkv_internal.h"
 
+#ifndef GKV_SCORE_NW
+#define GKV_SCORE_NW 8      // wavefronts per workgroup
+#endif
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
 
 template <int G, int WT>
 hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
-  constexpr int NW = 4;
+  constexpr int NW = GKV_SCORE_NW;
   constexpr int ROWS = G * 16 * WT;
   const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
   const int units = dm.L * dm.B * dm.Hkv;
@@ -223,7 +227,7 @@ bool gkv_score_mfma_supported(int g, int w) {
   const bool g_ok = (g == 1 || g == 2 || g == 4 || g == 5 || g == 7 || g == 8);
   if (!g_ok || (w != 16 && w != 32)) return false;
   const size_t rows = (size_t)g * w;                      // LDS the kernel needs; 64 KiB available
-  return rows * QSTR + sizeof(float) * (2 * rows + 2 * 4 * rows) <= 65536;
+  return rows * QSTR + sizeof(float) * (2 * rows + 2 * GKV_SCORE_NW * rows) <= 65536;
 }
 
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {

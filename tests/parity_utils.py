@@ -102,7 +102,7 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
     hkv = wl.n_kv_heads
     for t0 in range(0, n_steps, chunk):
         n = min(chunk, n_steps - t0)
-        q, k, v = tr.batch_steps(t0, n)
+        q, k, v = tr.batch_steps(t0, n, workers=8)
         qd = torch.from_numpy(q).to(dt).to(dev)
         kd = torch.from_numpy(k).to(dt).to(dev)
         vd = torch.from_numpy(v).to(dt).to(dev)

@@ -94,6 +94,16 @@ def test_cfg3_full_size_sampled_units():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+def test_cfg3_full_size_longer_run():
+    # 44 compressions at the benchmark's launch configuration, free-running between them
+    wl = CONFIGS["cfg3_28layer_b512"]
+    pairs = [(5, 1), (20, 6), (27, 4)]
+    _say("cfg3 full size, 6144 steps, 3 sampled pairs (12 units)")
+    st = run_parity(wl, 6144, pairs=pairs, check_state_every_event=False)
+    assert st["events"] == 44
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
 @pytest.mark.parametrize("budget,steps", [(1024, 1408), (2048, 2432)])
 def test_cfg4_budgets(budget, steps):
     wl = CONFIGS["cfg4_b512"].with_(n_layers=1, batch=2, budget=budget)
@@ -117,6 +127,13 @@ def test_cfg5_shape_heavy_tailed_keys():
     st = run_parity(wl, 1216, check_state_every_event=False)
     assert st["events"] == 3
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+def test_cfg5_shape_medium_batch_sampled():
+    # 4 layers x 8 sequences of the 40q/8kv shape (256 units), oracle on 3 sampled pairs
+    wl = CONFIGS["cfg5_large_batch"].with_(n_layers=4, batch=8)
+    st = run_parity(wl, 1280, pairs=[(0, 0), (2, 5), (3, 7)], check_state_every_event=False, chunk=64)
+    assert st["events"] == 4
 
 
 # ------------------------------------------------------------------ redundancy score (full G-KV)
