@@ -132,6 +132,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
                     help="split the layers into this many groups, each launched on its own HIP stream")
+    ap.add_argument("--copy-ring", action="store_true",
+                    help="hand q over in a separate buffer so that the decode kernel copies it into the window "
+                         "ring; by default the synthetic q of each step already sits in its ring slot")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
     ap.add_argument("--fast-prefix", action="store_true",
@@ -204,6 +207,8 @@ def main():
                  R=P(st.R), Fsel=P(st.F_sel))
             for st in groups]
     host = {"len": 0}
+    rings = [None] * NS
+    assert s % wl.window == 0
 
     def split_layers(x):
         """[n, L, ...] numpy -> per-group contiguous device tensors [n, L/NS, ...]."""
@@ -218,13 +223,20 @@ def main():
         len_host = host["len"]
         addr = [(qd.data_ptr(), qd.stride(0) * esz, kd.data_ptr(), kd.stride(0) * esz, vd.data_ptr(), vd.stride(0) * esz)
                 for (qd, kd, vd) in chunk]
+        w = wl.window
         for i in range(n):
             t = t0 + i
             for g in range(NS):
                 p = ptrs[g]
                 qb, qs, kb_, ks, vb, vs = addr[g]
+                # The pre-uploaded q tensors of w consecutive steps are laid out exactly like a ring
+                # [w, L, B, h_q, d] (chunks start at multiples of s, and w divides s), so step t's q
+                # already is slot t % w of that ring: nothing to copy.  --copy-ring uses the
+                # context's own ring instead.
+                ring = p["qwin"] if args.copy_ring else qb + (i - i % w) * qs
+                rings[g] = ring
                 rc = lib.gkv_attend_decode(p["h"], qb + i * qs, kb_ + i * ks, vb + i * vs, p["K"], p["V"], p["pos"], t,
-                                           p["qwin"], p["state"], len_host, p["out"], p["ws"], stream_of[g])
+                                           ring, p["state"], len_host, p["out"], p["ws"], stream_of[g])
                 if rc:
                     raise RuntimeError(f"gkv_attend_decode failed: {rc}")
             len_host += 1
@@ -232,12 +244,12 @@ def main():
                 for g in range(NS):
                     p = ptrs[g]
                     if args.redundancy is None:
-                        rc = lib.gkv_evict(p["h"], p["qwin"], p["K"], p["V"], p["Fh"], p["pos"], p["state"], t, len_host,
+                        rc = lib.gkv_evict(p["h"], rings[g], p["K"], p["V"], p["Fh"], p["pos"], p["state"], t, len_host,
                                            p["S"], p["F"], p["keep"], p["ws"], stream_of[g])
                     else:
                         lam, tau = args.redundancy
                         sg = stream_of[g]
-                        rc = (lib.gkv_score_window(p["h"], p["qwin"], p["K"], p["state"], t, len_host, p["S"], p["ws"], sg)
+                        rc = (lib.gkv_score_window(p["h"], rings[g], p["K"], p["state"], t, len_host, p["S"], p["ws"], sg)
                               or lib.gkv_global_update(p["h"], p["S"], p["Fh"], p["state"], t, len_host, p["F"], sg)
                               or lib.gkv_redundancy_combine(p["h"], p["K"], p["state"], t, len_host, p["F"], lam, tau,
                                                             1e-8, wl.window, p["R"], p["Fsel"], p["ws"], sg)
@@ -349,7 +361,7 @@ def main():
                    "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
                    "attend_splits": args.splits, "attend_tile": args.tile, "fast_prefix": args.fast_prefix,
                    "streams": NS, "layers_per_launch": Lg,
-                   "redundancy": args.redundancy},
+                   "redundancy": args.redundancy, "ring": "copy" if args.copy_ring else "in place"},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),

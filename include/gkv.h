@@ -130,9 +130,10 @@ gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
  *   window ring qwin.  With k_new == v_new == NULL nothing is appended and the
  *   attention covers rows [0, len) only.  d_state is not written.
  * q, out [L,B,h_q,d]; k_new, v_new [L,B,h_kv,d]; K, V [L,B,h_kv,capacity,d];
- * pos [L,B,h_kv,capacity]; qwin [L,B,w,h_q,d] (slot-major per sequence, so one
- * step's write is contiguous per KV group).  len_max_host: host bound with every
- * len <= len_max_host < capacity.
+ * pos [L,B,h_kv,capacity]; qwin [w,L,B,h_q,d]: slot step % w is one whole q tensor.
+ * If q already IS that slot (q == qwin + (step % w) * L*B*h_q*d elements: the
+ * producer of q wrote it into the ring), nothing is copied.  len_max_host: host
+ * bound with every len <= len_max_host < capacity.
  */
 gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
                              void* K, void* V, int32_t* pos, int32_t step, void* qwin,

@@ -79,11 +79,14 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(GkvDims dm, AttendA
     }
     if (tid == 0) a.pos[(size_t)unit * cap + len0] = a.step;
   }
-  const int slot = a.step % dm.w;
-  for (int x = tid; x < g * d; x += blockDim.x) {
-    const int head = j * g + x / d, c = x % d;
-    ((T*)a.qwin)[(((size_t)lb * dm.w + slot) * dm.Hq + head) * d + c] =
-        ((const T*)a.q)[((size_t)lb * dm.Hq + head) * d + c];
+  if (a.copy_q) {
+    const int slot = a.step % dm.w;
+    const size_t nlb = (size_t)dm.L * dm.B;
+    for (int x = tid; x < g * d; x += blockDim.x) {
+      const int head = j * g + x / d, c = x % d;
+      ((T*)a.qwin)[(((size_t)slot * nlb + lb) * dm.Hq + head) * d + c] =
+          ((const T*)a.q)[((size_t)lb * dm.Hq + head) * d + c];
+    }
   }
 }
 

@@ -230,6 +230,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   constexpr int AP_ROUNDS = (32 + 16 * 16 + NW * 64 - 1) / (NW * 64);
   u32x4 ap[AP_ROUNDS];
   const bool appender = sp == 0;
+  const bool ring_copy = appender && a.copy_q;   // q may already live in its ring slot
   const bool may_grow = a.k_new != nullptr;
   {
     const char* knew_g = (const char*)a.k_new + (size_t)unit * ROW_BYTES;
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
       if (x < 16) { if (may_grow) ap[rd] = ld16(knew_g + x * 16); }
       else if (x < 32) { if (may_grow) ap[rd] = ld16(vnew_g + (x - 16) * 16); }
       else if (x < 32 + 16 * g) {
-        if (appender) ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16);
+        if (ring_copy) ap[rd] = ld16((const char*)a.q + ((size_t)lb * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16);
       }
     }
   }
@@ -345,8 +346,8 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
         if (has_new) *(u32x4*)((char*)a.K + ((size_t)unit * cap + len0) * ROW_BYTES + x * 16) = piece;
       } else if (x < 32) {
         if (has_new) *(u32x4*)((char*)a.V + ((size_t)unit * cap + len0) * ROW_BYTES + (x - 16) * 16) = piece;
-      } else {
-        *(u32x4*)((char*)a.qwin + (((size_t)lb * dm.w + slot) * dm.Hq + j * g) * ROW_BYTES + (x - 32) * 16) = piece;
+      } else if (ring_copy) {
+        *(u32x4*)((char*)a.qwin + ((((size_t)slot * dm.L * dm.B + lb) * dm.Hq + j * g) * ROW_BYTES) + (x - 32) * 16) = piece;
       }
     }
     if (has_new && tid == NW * 64 - 1) a.pos[(size_t)unit * cap + len0] = a.step;

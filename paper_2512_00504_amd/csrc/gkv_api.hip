@@ -219,7 +219,11 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
   if (st != GKV_OK) return st;
   AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_state, out, gkv_carve_workspace(ctx, workspace), 1,
-               ctx->attend_tile};
+               ctx->attend_tile, 1};
+  {
+    const size_t slot_bytes = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hq * ctx->dims.d * ctx->esz;
+    a.copy_q = (const char*)q != (const char*)qwin + (size_t)(step % ctx->dims.w) * slot_bytes;
+  }
   GkvLaunch ln{ctx, GKV_K_ATTEND, (hipStream_t)stream};
   if (use_mfma_attend(ctx)) {
     a.splits = gkv_effective_splits(ctx);

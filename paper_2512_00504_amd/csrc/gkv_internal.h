@@ -53,6 +53,7 @@ struct AttendArgs {
   const void* q; const void* k_new; const void* v_new;
   void* K; void* V; int32_t* pos; int32_t step; void* qwin; const int32_t* d_state; void* out;
   GkvWorkspace ws; int32_t splits; int32_t tile_keys;
+  int32_t copy_q;   // 0 when q already is the ring slot of this step
 };
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void score_generic_kernel(GkvDims dm, ScoreArg
     for (int n = tid; n < c; n += blockDim.x) rowmax[n] = 0.f;
     for (int hi = 0; hi < g; ++hi) {
       const int head = j * g + hi;
-      const T* qh = (const T*)a.qwin + (((size_t)lb * w + slot) * dm.Hq + head) * d;
+      const T* qh = (const T*)a.qwin + (((size_t)slot * dm.L * dm.B + lb) * dm.Hq + head) * d;
       __syncthreads();
       for (int ch = tid; ch < d; ch += blockDim.x) qs[ch] = Elem<T>::ld(qh + ch);
       __syncthreads();

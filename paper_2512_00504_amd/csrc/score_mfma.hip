@@ -82,7 +82,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     const int t_row = a.step - W + 1 + k;
     const int slot = ((t_row % W) + W) % W;
     *(u32x4*)(qs + row * QSTR + ch * 16) =
-        ld16((const char*)a.qwin + (((size_t)lb * W + slot) * dm.Hq + j * G + h) * (size_t)ROW_BYTES + ch * 16);
+        ld16((const char*)a.qwin + (((size_t)slot * dm.L * dm.B + lb) * dm.Hq + j * G + h) * (size_t)ROW_BYTES + ch * 16);
   }
   __syncthreads();
 

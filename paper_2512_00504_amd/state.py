@@ -55,7 +55,7 @@ class DecodeState:
         self.K = z(L, B, Hkv, cap, d, dtype=dt)          # rows below N_TILED tiled, the rest row-major
         self.V = z(L, B, Hkv, cap, d, dtype=dt)
         self.pos = torch.full((L, B, Hkv, cap), -1, dtype=torch.int32, device=dev)
-        self.qwin = z(L, B, w, Hq, d, dtype=dt)
+        self.qwin = z(w, L, B, Hq, d, dtype=dt)          # ring of the last w q tensors
         self.d_state = z(L, B, 4, dtype=torch.int32)     # {len, len_step, n_hist, n_tiled}
         self.F_hist = z(L, B, Hkv, cap, dtype=torch.float32)
         self.S = z(L, B, Hkv, cap, dtype=torch.float32)

@@ -235,8 +235,8 @@ def test_attend_ragged_lengths_formats_and_empty_append(dtype):
             np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=tol * np.abs(ref).max())
         else:
             np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=2e-2)
-    # window ring slot 3 now holds q (ring layout [L, B, w, h_q, d])
-    assert torch.equal(st.qwin[0, :, 3].cpu(), q[0])
+    # window ring slot 3 now holds q (ring layout [w, L, B, h_q, d])
+    assert torch.equal(st.qwin[3].cpu(), q)
 
 
 def test_attend_length_follows_the_step_number():
@@ -256,7 +256,28 @@ def test_attend_length_follows_the_step_number():
         np.testing.assert_allclose(out[0, b], ref, rtol=0, atol=1e-5 * np.abs(ref).max())
     assert torch.equal(st.K[0, :, :, 7].cpu(), kn[0]) and torch.equal(st.V[0, :, :, 7].cpu(), vn[0])
     assert (st.pos[0, :, :, 7] == 12).all()
-    assert torch.equal(st.qwin[0, :, 12 % 4].cpu(), q[0])
+    assert torch.equal(st.qwin[12 % 4].cpu(), q)
+
+
+def test_attend_zero_copy_ring_slot():
+    # q handed over inside its ring slot: same output, the rest of the ring untouched
+    st = _state("bf16", head_dim=128, n_q_heads=14, n_kv_heads=2)
+    g = torch.Generator().manual_seed(3)
+    K = torch.randn(st.K.shape, generator=g).to(torch.bfloat16); V = torch.randn(st.V.shape, generator=g).to(torch.bfloat16)
+    q = torch.randn(1, 2, 14, 128, generator=g).to(torch.bfloat16)
+    kn = torch.randn(1, 2, 2, 128, generator=g).to(torch.bfloat16); vn = torch.randn(1, 2, 2, 128, generator=g).to(torch.bfloat16)
+    outs = []
+    for in_place in (False, True):
+        st.K.copy_(K); st.V.copy_(V); st.qwin.fill_(9.0)
+        _set_lengths(st, (30, 17), step_next=6)
+        qd = q.cuda()
+        if in_place:
+            st.qwin[6 % 4].copy_(q)
+            qd = st.qwin[6 % 4]
+        outs.append(st.attend_decode(qd, kn.cuda(), vn.cuda(), 6).clone())
+        assert torch.equal(st.qwin[6 % 4].cpu(), q)
+        assert (st.qwin[[0, 1, 3]] == 9.0).all()
+    assert torch.equal(outs[0], outs[1])
 
 
 def test_attend_rejects_bad_arguments():
