@@ -191,15 +191,15 @@ def main():
     # Every decode step launches every group; units are independent, so the groups' kernels may
     # overlap and one group's kernel boundary (launch, first-load latency, final stores) is
     # covered by the other group's streaming.  NS = 1 is the plain one-launch-per-step form.
-    NS = max(1, args.streams)
-    while wl.n_layers % NS:
-        NS -= 1
-    Lg = wl.n_layers // NS
+    NS = max(1, min(args.streams, wl.n_layers))
+    bounds = [wl.n_layers * g // NS for g in range(NS + 1)]          # as even as possible
+    Lgs = [bounds[g + 1] - bounds[g] for g in range(NS)]
+    Lg = max(Lgs)
     tr = Trace(wl)
     dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     esz = 2 if wl.dtype == "bf16" else 4
     streams = [torch.cuda.Stream(device=dev) for _ in range(NS)]
-    groups = [DecodeState.from_workload(wl.with_(n_layers=Lg), device=dev, params=params) for _ in range(NS)]
+    groups = [DecodeState.from_workload(wl.with_(n_layers=Lgs[g]), device=dev, params=params) for g in range(NS)]
     lib = groups[0].ctx.lib
     P = lambda t: ctypes.c_void_p(t.data_ptr())
     ptrs = [dict(h=st.ctx.h, K=P(st.K), V=P(st.V), pos=P(st.pos), qwin=P(st.qwin), state=P(st.d_state),
@@ -211,8 +211,8 @@ def main():
     assert s % wl.window == 0
 
     def split_layers(x):
-        """[n, L, ...] numpy -> per-group contiguous device tensors [n, L/NS, ...]."""
-        return [torch.from_numpy(x[:, g * Lg:(g + 1) * Lg]).to(dt).to(dev).contiguous() for g in range(NS)]
+        """[n, L, ...] numpy -> per-group contiguous device tensors [n, layers of the group, ...]."""
+        return [torch.from_numpy(x[:, bounds[g]:bounds[g + 1]]).to(dt).to(dev).contiguous() for g in range(NS)]
 
     def upload(t0, n):
         q, k, v = tr.batch_steps(t0, n, workers=8)
