@@ -129,6 +129,21 @@ def test_cfg5_shape_heavy_tailed_keys():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+@pytest.mark.parametrize("shape", [
+    dict(n_q_heads=4, n_kv_heads=4, budget=96, window=16, interval=32),          # MHA, g = 1
+    dict(n_q_heads=16, n_kv_heads=2, budget=100, window=16, interval=40),        # g = 8, b and s not multiples of 16, w does not divide s
+    dict(n_q_heads=32, n_kv_heads=2, budget=80, window=16, interval=16),         # g = 16 (generic score kernel), w = s
+    dict(n_q_heads=12, n_kv_heads=4, budget=72, window=32, interval=56),         # g = 3 (generic score), w = 32
+    dict(n_q_heads=10, n_kv_heads=2, budget=64, window=32, interval=32, head_dim=64),   # d = 64: generic everywhere
+])
+def test_odd_shapes_bf16(shape):
+    kw = dict(n_layers=2, batch=3, head_dim=128, dtype="bf16", n_steps=400, seed=21)
+    kw.update(shape)
+    wl = CONFIGS["cfg2_single_layer"].with_(**kw)
+    st = run_parity(wl, wl.n_steps, chunk=64)
+    assert st["events"] >= 3
+
+
 def test_cfg5_shape_medium_batch_sampled():
     # 4 layers x 8 sequences of the 40q/8kv shape (256 units), oracle on 3 sampled pairs
     wl = CONFIGS["cfg5_large_batch"].with_(n_layers=4, batch=8)
