@@ -15,7 +15,7 @@ TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 OUT_TOL = {"f32": ("rel", 1e-5), "bf16": ("abs", 2e-2)}
 SWAP_REL = 1e-6          # kept sets may differ only between scores closer than this (relative)
 SWAP_TINY = 1e-30        # ... or both below anything fp32 softmax can resolve
-SCORE_REL = 2e-5         # fp32 score arithmetic on exact inputs vs fp64
+SCORE_REL = 1e-5         # fp32 score arithmetic on exact inputs vs fp64 (measured worst: 1.9e-6)
 
 
 def make_oracle(wl, **kw):
