@@ -80,9 +80,9 @@ typedef enum { GKV_COMBINE_MAX = 0, GKV_COMBINE_AVG = 1, GKV_COMBINE_SUM = 2 } g
 typedef struct gkv_config {
   int32_t n_layers, batch;          /* L, B */
   int32_t n_q_heads, n_kv_heads;    /* h_q, h_kv; h_q % h_kv == 0 */
-  int32_t head_dim;                 /* d; multiple of 16/sizeof(element) */
+  int32_t head_dim;                 /* d; multiple of 16/sizeof(element), at most 1024 bytes per row */
   int32_t budget, window, interval; /* b, w, s;  w <= s, w < b */
-  int32_t capacity;                 /* rows per KV head; >= b + s, multiple of 32 */
+  int32_t capacity;                 /* rows per KV head; >= b + s, multiple of 32, at most 4096 */
   int32_t dtype;                    /* gkv_dtype */
   int32_t combine;                  /* gkv_combine */
   float alpha;                      /* memory-decay rate in [0,1]; 0 = local score only */
@@ -114,8 +114,8 @@ gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_el
                            size_t* kv_bytes, size_t* score_bytes);
 int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_t n_tiled);
 
-/* Tuning knobs (host only): "attend_splits" (0 = automatic; set before
- * gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
+/* Tuning knobs (host only): "attend_splits" (workgroups per unit in the matrix-core
+ * attend kernel; 0 = default = 1; set before gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
  * the matrix-core attend kernel), "force_generic" (1 = use the plain vector-ALU
  * kernels even where matrix-core kernels exist). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
