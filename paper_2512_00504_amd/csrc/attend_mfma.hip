@@ -268,7 +268,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   if (it < n_iter) issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
   // stage: 16-byte pieces [0,16) k_new, [16,32) v_new, [32, 32+16g) q rows; kept in LDS, not in
   // registers, until they are stored at the end
-  char* stage = (char*)(smem + NW * g * OSTR + NW * 16 + NW * 64);
+  char* stage = (char*)(smem + NW * g * OSTR + NW * 16 + NW * 16);
   const char* knew = stage;
   const char* vnew = stage + ROW_BYTES;
 #pragma unroll
@@ -289,7 +289,10 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   // ---- merge the wavefronts of this workgroup -------------------------------------------------
   float* so = smem;                         // [NW][g][OSTR]
   float* sm = so + NW * g * OSTR;           // [NW][16]
-  float* sl = sm + NW * 16;                 // [NW][4][16]
+  float* sl = sm + NW * 16;                 // [NW][16]
+  float l_tot = l_run;                      // the 4 lanes of a head hold partial sums
+  l_tot += __shfl_xor(l_tot, 16);
+  l_tot += __shfl_xor(l_tot, 32);
   if (r < g) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -297,38 +300,37 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
       *(f32x4*)dst = f32x4{oacc[0][e], oacc[1][e], oacc[2][e], oacc[3][e]};
       *(f32x4*)(dst + 4) = f32x4{oacc[4][e], oacc[5][e], oacc[6][e], oacc[7][e]};
     }
-    sl[(wave * 4 + kb) * 16 + r] = l_run;
-    if (kb == 0) sm[wave * 16 + r] = m_run;
+    if (kb == 0) { sm[wave * 16 + r] = m_run; sl[wave * 16 + r] = l_tot; }
   }
   __syncthreads();
 
+  // one thread per (head, 4 channels): a single round for g <= 8 with 256 threads
   uint16_t* out = (uint16_t*)a.out + ((size_t)lb * dm.Hq + j * g) * D;
   float* part = a.ws.partials + (size_t)(unit * splits + sp) * g * PSTR;
-  for (int x = tid; x < g * 64; x += NW * 64) {
-    const int h = x >> 6, cp = x & 63;
-    float M = sm[h];
+  for (int x = tid; x < g * 32; x += NW * 64) {
+    const int h = x >> 5, c4 = (x & 31) * 4;
+    float mw[NW];
+    float M = -1e30f;
 #pragma unroll
-    for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, sm[wv * 16 + h]);
-    float Lsum = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int wv = 0; wv < NW; ++wv) { mw[wv] = sm[wv * 16 + h]; M = fmaxf(M, mw[wv]); }
+    float Lsum = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int wv = 0; wv < NW; ++wv) {
-      const float f = __builtin_amdgcn_exp2f(sm[wv * 16 + h] - M);
-      const float lw = (sl[(wv * 4 + 0) * 16 + h] + sl[(wv * 4 + 1) * 16 + h]) +
-                       (sl[(wv * 4 + 2) * 16 + h] + sl[(wv * 4 + 3) * 16 + h]);
-      Lsum += lw * f;
-      o0 += so[(wv * g + h) * OSTR + 2 * cp] * f;
-      o1 += so[(wv * g + h) * OSTR + 2 * cp + 1] * f;
+      const float f = __builtin_amdgcn_exp2f(mw[wv] - M);
+      Lsum += sl[wv * 16 + h] * f;
+      o += *(const f32x4*)(so + (wv * g + h) * OSTR + c4) * f;
     }
     if (splits == 1) {
-      const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
-      const uint32_t packed = (uint32_t)float_to_bf16_bits(o0 * inv) |
-                              ((uint32_t)float_to_bf16_bits(o1 * inv) << 16);
-      *(uint32_t*)(out + h * D + 2 * cp) = packed;
+      const float inv = Lsum > 0.f ? __builtin_amdgcn_rcpf(Lsum) : 0.f;   // the result is rounded to bf16 anyway
+      uint2 packed;
+      packed.x = (uint32_t)float_to_bf16_bits(o[0] * inv) | ((uint32_t)float_to_bf16_bits(o[1] * inv) << 16);
+      packed.y = (uint32_t)float_to_bf16_bits(o[2] * inv) | ((uint32_t)float_to_bf16_bits(o[3] * inv) << 16);
+      *(uint2*)(out + h * D + c4) = packed;
     } else {
       float* ph = part + h * PSTR;
-      ph[2 * cp] = o0;
-      ph[2 * cp + 1] = o1;
-      if (cp == 0) { ph[D] = M; ph[D + 1] = Lsum; }
+      ph[c4] = o[0]; ph[c4 + 1] = o[1]; ph[c4 + 2] = o[2]; ph[c4 + 3] = o[3];
+      if (c4 == 0) { ph[D] = M; ph[D + 1] = Lsum; }
     }
   }
 
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a) {
   constexpr int NW = 4;
   const int units = dm.L * dm.B * dm.Hkv;
-  const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 64) + (32 + 16 * dm.g) * 16;
+  const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 16) + (32 + 16 * dm.g) * 16;
   if (a.tile_keys == 32)
     return gkv_launch(ln, attend_mfma_kernel<NW, 2>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
   return gkv_launch(ln, attend_mfma_kernel<NW, 1>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
