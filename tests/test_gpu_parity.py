@@ -144,6 +144,26 @@ def test_odd_shapes_bf16(shape):
     assert st["events"] >= 3
 
 
+@pytest.mark.parametrize("params", [None, {"attend_splits": 3}, {"force_generic": 1}])
+def test_results_are_deterministic(params):
+    # same inputs, same bits: outputs, kept indices, scores and cache contents of two runs
+    from gkv_traces import Trace
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2, budget=96, interval=32, n_steps=160)
+    tr = Trace(wl)
+    q, k, v = [torch.from_numpy(x).to(torch.bfloat16).cuda() for x in tr.batch_steps(0, wl.n_steps)]
+    runs = []
+    for _ in range(2):
+        st = DecodeState.from_workload(wl, params=params)
+        outs = []
+        for t in range(wl.n_steps):
+            outs.append(st.attend_decode(q[t], k[t], v[t], t).clone())
+            if st.is_trigger(t):
+                st.evict(t)
+        runs.append((torch.stack(outs), st.keep_idx.clone(), st.F.clone(), st.K.clone(), st.V.clone(), st.F_hist.clone()))
+    for x, y in zip(*runs):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+
+
 def test_cfg5_shape_medium_batch_sampled():
     # 4 layers x 8 sequences of the 40q/8kv shape (256 units), oracle on 3 sampled pairs
     wl = CONFIGS["cfg5_large_batch"].with_(n_layers=4, batch=8)
