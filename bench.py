@@ -347,6 +347,7 @@ def main():
         us = per_kernel[name]["avg_us"]
         per_kernel[name]["algorithmic_MB"] = alg[name] / NS / 1e6
         per_kernel[name]["GBps"] = (alg[name] / NS / (us * 1e-6) / 1e9) if us else None
+        per_kernel[name]["hbm_frac"] = (per_kernel[name]["GBps"] / HBM_PEAK_GBS) if us else None
     bytes_per_step = alg["attend"] + (alg["score"] + alg["global"] + alg["topk"] + alg["compact"]) / s
     tokens_per_s = wl.batch * K / elapsed
     out = {
