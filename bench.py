@@ -132,9 +132,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
                     help="split the layers into this many groups, each launched on its own HIP stream")
-    ap.add_argument("--copy-ring", action="store_true",
-                    help="hand q over in a separate buffer so that the decode kernel copies it into the window "
-                         "ring; by default the synthetic q of each step already sits in its ring slot")
+    ap.add_argument("--ring-in-place", action="store_true",
+                    help="treat the pre-uploaded q tensors as the window ring itself (q of step t already is slot "
+                         "t %% w), so the decode kernel copies nothing; by default q is copied into the context's ring")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
     ap.add_argument("--fast-prefix", action="store_true",
@@ -229,11 +229,11 @@ def main():
             for g in range(NS):
                 p = ptrs[g]
                 qb, qs, kb_, ks, vb, vs = addr[g]
-                # The pre-uploaded q tensors of w consecutive steps are laid out exactly like a ring
-                # [w, L, B, h_q, d] (chunks start at multiples of s, and w divides s), so step t's q
-                # already is slot t % w of that ring: nothing to copy.  --copy-ring uses the
-                # context's own ring instead.
-                ring = p["qwin"] if args.copy_ring else qb + (i - i % w) * qs
+                # Default: q is copied into the context's own ring by the decode kernel.
+                # --ring-in-place: the pre-uploaded q tensors of w consecutive steps are laid out
+                # exactly like a ring [w, L, B, h_q, d] (chunks start at multiples of s, and w divides
+                # s), so step t's q already is slot t % w of that ring and nothing is copied.
+                ring = qb + (i - i % w) * qs if args.ring_in_place else p["qwin"]
                 rings[g] = ring
                 rc = lib.gkv_attend_decode(p["h"], qb + i * qs, kb_ + i * ks, vb + i * vs, p["K"], p["V"], p["pos"], t,
                                            ring, p["state"], len_host, p["out"], p["ws"], stream_of[g])
@@ -362,7 +362,7 @@ def main():
                    "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
                    "attend_splits": args.splits, "attend_tile": args.tile, "fast_prefix": args.fast_prefix,
                    "streams": NS, "layers_per_launch": Lg,
-                   "redundancy": args.redundancy, "ring": "copy" if args.copy_ring else "in place"},
+                   "redundancy": args.redundancy, "ring": "in place" if args.ring_in_place else "copy"},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),
