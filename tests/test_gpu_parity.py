@@ -402,6 +402,35 @@ def test_select_topk_ties_nan_and_brute_force():
     assert 7 in odd.tolist()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_select_topk_random_shapes_signs_and_ties(seed):
+    # seeded sweep: budgets/windows/lengths that are not round numbers, negative and tied scores,
+    # several decimal granularities; the GPU must equal the oracle's (score desc, index asc) rule
+    rng = np.random.default_rng(100 + seed)
+    b = int(rng.integers(40, 300)); w = int(rng.integers(1, 33)); s_ = int(rng.integers(max(w, 8), 200))
+    cap = (b + s_ + 31) // 32 * 32
+    st = _state(budget=b, window=w, interval=s_, capacity=cap, n_q_heads=2, n_kv_heads=2)
+    lens = (int(rng.integers(b + 1, b + s_ + 1)), b + s_)
+    _set_lengths(st, lens, step_next=1000)
+    F = np.zeros((1, 2, 2, cap), np.float32)
+    for bb in range(2):
+        for j in range(2):
+            x = rng.standard_normal(cap).astype(np.float32)
+            mode = (seed + bb + 2 * j) % 4
+            if mode == 1: x = np.round(x, 1)                      # heavy ties, both signs
+            elif mode == 2: x = np.abs(np.round(x, 0))            # a handful of distinct values
+            elif mode == 3: x[rng.integers(0, cap, 20)] = 0.0; x[rng.integers(0, cap, 5)] = -0.0
+            F[0, bb, j] = x
+    st.F.copy_(torch.from_numpy(F))
+    st.select_topk(999)
+    keep = st.keep_idx.cpu().numpy()
+    for bb in range(2):
+        c = lens[bb] - w
+        for j in range(2):
+            ref = O.select_topk(F[0, bb, j, :c][None].astype(np.float64), b - w)[0]
+            np.testing.assert_array_equal(keep[0, bb, j], ref)
+
+
 @pytest.mark.parametrize("pattern", ["front", "back", "alternate", "random"])
 @pytest.mark.parametrize("dtype,nt_old", [("f32", 0), ("bf16", 0), ("bf16", 160), ("f32", 96)])
 def test_compact_adversarial_keep_patterns(pattern, dtype, nt_old):
