@@ -222,9 +222,7 @@ gkv_status gkv_pool_scores(gkv_ctx* ctx, const float* F, const int32_t* d_state,
 gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const int32_t* pos,
                                  const int32_t* d_state, int32_t step, int32_t* evicted, void* stream);
 
-/* One compression: what the four calls above do in order, on caller-provided S, F,
- * keep_idx, with the local and the global score formed in one launch (S never
- * leaves the chip between them; it is still written out for inspection). */
+/* The four compression calls above in order, on caller-provided S, F, keep_idx. */
 gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
                      int32_t* d_state, int32_t step, int32_t len_max_host,
                      float* S, float* F, int32_t* keep_idx, void* workspace, void* stream);

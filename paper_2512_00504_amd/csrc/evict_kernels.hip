@@ -49,7 +49,14 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
   mx = block_max(mx, red);
   for (int n = tid; n < c; n += 256) {
     const float sn = mx > 0.f ? Su[n] / mx : 0.f;
-    Fu[n] = global_combine(sn, n < n_hist ? Hu[n] : 0.f, n < n_hist, dm.alpha, dm.combine);
+    float f = sn;
+    if (n < n_hist) {
+      const float h = dm.alpha * Hu[n];
+      f = dm.combine == GKV_COMBINE_MAX ? fmaxf(h, sn)
+        : dm.combine == GKV_COMBINE_AVG ? h + (1.f - dm.alpha) * sn
+                                        : h + sn;
+    }
+    Fu[n] = f;
   }
 }
 

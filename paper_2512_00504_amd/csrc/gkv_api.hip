@@ -200,7 +200,7 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
 // ---- the five calls -----------------------------------------------------------------------------
 static bool use_mfma_attend(const gkv_ctx* ctx) { return ctx->mfma_ok && !ctx->force_generic; }
 static bool use_mfma_score(const gkv_ctx* ctx) {
-  return ctx->mfma_ok && !ctx->force_generic && gkv_score_mfma_supported(ctx->dims.g, ctx->dims.w, ctx->dims.cap);
+  return ctx->mfma_ok && !ctx->force_generic && gkv_score_mfma_supported(ctx->dims.g, ctx->dims.w);
 }
 static gkv_status check_len(const gkv_ctx* ctx, int32_t len_max_host, bool appending) {
   if (len_max_host < 0) return GKV_ERR_INVALID_ARG;
@@ -232,15 +232,6 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   return hip_status(gkv_launch_attend_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 
-// Window score, optionally with the global-score tail fused in (F_hist and F_out both set).
-static gkv_status score_launch(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state, int32_t step,
-                               float* S, const float* F_hist, float* F_out, void* stream) {
-  ScoreArgs a{qwin, K, d_state, step, S, F_hist, F_out};
-  GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
-  if (use_mfma_score(ctx)) return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
-  return hip_status(gkv_launch_score_generic(ln, ctx->dims, ctx->cfg.dtype, a));
-}
-
 extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state,
                                        int32_t step, int32_t len_max_host, float* S,
                                        void* workspace, void* stream) {
@@ -248,7 +239,10 @@ extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const voi
   if (!ctx || !qwin || !K || !d_state || !S || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  return score_launch(ctx, qwin, K, d_state, step, S, nullptr, nullptr, stream);
+  ScoreArgs a{qwin, K, d_state, step, S};
+  GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
+  if (use_mfma_score(ctx)) return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
+  return hip_status(gkv_launch_score_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 
 extern "C" gkv_status gkv_global_update(gkv_ctx* ctx, const float* S, const float* F_hist,
@@ -289,8 +283,9 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
   if (F == F_hist) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  // score and global score in one launch: S stays in LDS between the two
-  st = score_launch(ctx, qwin, K, d_state, step, S, F_hist, F, stream);
+  st = gkv_score_window(ctx, qwin, K, d_state, step, len_max_host, S, workspace, stream);
+  if (st != GKV_OK) return st;
+  st = gkv_global_update(ctx, S, F_hist, d_state, step, len_max_host, F, stream);
   if (st != GKV_OK) return st;
   st = gkv_select_topk(ctx, F, d_state, step, len_max_host, keep_idx, workspace, stream);
   if (st != GKV_OK) return st;

@@ -60,11 +60,10 @@ hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const 
 
 struct ScoreArgs {
   const void* qwin; const void* K; const int32_t* d_state; int32_t step; float* S;
-  const float* F_hist; float* F_out;   // both set: the kernel also forms the global score (fused tail)
 };
 hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a);
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a);
-bool gkv_score_mfma_supported(int g, int w, int cap);
+bool gkv_score_mfma_supported(int g, int w);
 
 hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
                                     const float* F_hist, const int32_t* d_state, int32_t step, float* F_out);
@@ -127,14 +126,6 @@ template <int EPC>
 __device__ __forceinline__ int k_elem_offset(int n, int c, int d, int n_tiled) {
   if (n >= n_tiled) return n * d + c;
   return (n >> 4) * 16 * d + (c / EPC) * (16 * EPC) + (n & 15) * EPC + (c % EPC);
-}
-
-// Global score of one candidate (paper, Section 4): sn is the local score over its per-head
-// maximum, h_prev the recorded score; entries without history take sn unchanged.
-__device__ __forceinline__ float global_combine(float sn, float h_prev, bool has_hist, float alpha, int form) {
-  if (!has_hist) return sn;
-  const float h = alpha * h_prev;
-  return form == GKV_COMBINE_MAX ? fmaxf(h, sn) : form == GKV_COMBINE_AVG ? h + (1.f - alpha) * sn : h + sn;
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

@@ -66,26 +66,10 @@ __global__ void score_generic_kernel(GkvDims dm, ScoreArgs a) {
   }
   __syncthreads();
   float* So = a.S + (size_t)unit * cap;
-  float mx = 0.f;
   for (int n = tid; n < c; n += blockDim.x) {
     float tot = 0.f;
     for (int wv = 0; wv < nw; ++wv) tot += smem[wv * per_wave + 2 * (size_t)cap + n];
-    const float sv = tot / (float)w;
-    So[n] = sv;
-    smem[n] = sv;                            // wavefront 0's z region, free by now
-    mx = fmaxf(mx, sv);
-  }
-  // fused tail: global score of the candidates (Section 4)
-  if (a.F_out != nullptr) {
-    float* red = smem + cap;                 // wavefront 0's rowmax region, free by now
-    mx = block_max(mx, red);
-    const int n_hist = st.n_hist < 0 ? 0 : (st.n_hist > c ? c : st.n_hist);
-    const float* Hu = a.F_hist + (size_t)unit * cap;
-    float* Fu = a.F_out + (size_t)unit * cap;
-    for (int n = tid; n < c; n += blockDim.x) {
-      const float sn = mx > 0.f ? smem[n] / mx : 0.f;
-      Fu[n] = global_combine(sn, n < n_hist ? Hu[n] : 0.f, n < n_hist, dm.alpha, dm.combine);
-    }
+    So[n] = tot / (float)w;
   }
 }
 

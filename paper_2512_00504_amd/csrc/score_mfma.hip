@@ -53,8 +53,7 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
   for (int c = 0; c < 4; ++c) kA[c] = ld16(p + c * step_off);
 }
 
-// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float redM[NW*G*w]; float redS[NW*G*w];
-//              float sbuf[cap]; float red[8]
+// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float redM[NW*G*w]; float redS[NW*G*w]
 template <int NW, int G, int WT>
 __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -75,8 +74,6 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   float* rowZ = rowM + ROWS;
   float* redM = rowZ + ROWS;
   float* redS = redM + NW * ROWS;
-  float* sbuf = redS + NW * ROWS;           // S of this unit, for the fused global-score tail
-  float* red = sbuf + cap;
 
   // stage the window queries: LDS row h*W + k holds head h, window row k (k-th oldest)
   for (int x = tid; x < ROWS * 16; x += NW * 64) {
@@ -210,22 +207,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
       v += __shfl_xor(v, 4);
       v += __shfl_xor(v, 8);
       const int key = 16 * T + 4 * kb + e;
-      if (r == 0 && key < cc) { const float sv = v / wf; So[key] = sv; sbuf[key] = sv; }
-    }
-  }
-
-  // ---- fused tail: global score of the candidates (Section 4), S still in LDS ----------------
-  if (a.F_out != nullptr) {
-    __syncthreads();
-    float mx = 0.f;
-    for (int n = tid; n < cc; n += NW * 64) mx = fmaxf(mx, sbuf[n]);
-    mx = block_max(mx, red);
-    const int n_hist = seq.n_hist < 0 ? 0 : (seq.n_hist > cc ? cc : seq.n_hist);
-    const float* Hu = a.F_hist + (size_t)unit * cap;
-    float* Fu = a.F_out + (size_t)unit * cap;
-    for (int n = tid; n < cc; n += NW * 64) {
-      const float sn = mx > 0.f ? sbuf[n] / mx : 0.f;
-      Fu[n] = global_combine(sn, n < n_hist ? Hu[n] : 0.f, n < n_hist, dm.alpha, dm.combine);
+      if (r == 0 && key < cc) So[key] = v / wf;
     }
   }
 }
@@ -234,18 +216,18 @@ template <int G, int WT>
 hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
   constexpr int NW = GKV_SCORE_NW;
   constexpr int ROWS = G * 16 * WT;
-  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS + dm.cap + 8);
+  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
   const int units = dm.L * dm.B * dm.Hkv;
   return gkv_launch(ln, score_mfma_kernel<NW, G, WT>, dim3(units), dim3(NW * 64), shmem, dm, a);
 }
 
 }  // namespace
 
-bool gkv_score_mfma_supported(int g, int w, int cap) {
+bool gkv_score_mfma_supported(int g, int w) {
   const bool g_ok = (g == 1 || g == 2 || g == 4 || g == 5 || g == 7 || g == 8);
   if (!g_ok || (w != 16 && w != 32)) return false;
   const size_t rows = (size_t)g * w;                      // LDS the kernel needs; 64 KiB available
-  return rows * QSTR + sizeof(float) * (2 * rows + 2 * GKV_SCORE_NW * rows + cap + 8) <= 65536;
+  return rows * QSTR + sizeof(float) * (2 * rows + 2 * GKV_SCORE_NW * rows) <= 65536;
 }
 
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
