@@ -76,6 +76,14 @@ def test_cfg3_shape_small_batch_many_layers():
     assert st["events"] == 4
 
 
+@pytest.mark.parametrize("form", ["max", "avg", "sum"])
+def test_cfg3_shape_evict_entry_point(form):
+    # gkv_evict (the four compression calls in one entry point) on the matrix-core kernels
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2, combine=form)
+    st = run_parity(wl, 1024, fused_evict=True, check_state_every_event=False)
+    assert st["events"] == 4
+
+
 def test_cfg3_shape_32_key_slices():
     # the other slice size of the matrix-core attend kernel
     wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
