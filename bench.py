@@ -139,6 +139,8 @@ def main():
     ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
     ap.add_argument("--fast-prefix", action="store_true",
                     help="fill the cache prefix by repeating the first s generated steps (for the largest workloads)")
+    ap.add_argument("--no-full-launch", action="store_true",
+                    help="skip the extra pass that times the attend kernel launched once for all layers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--cpu-worker", nargs=6, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS", "COMBINE", "ALPHA"))
@@ -320,6 +322,35 @@ def main():
         per_kernel[name] = {"launches": n, "avg_us": (1e3 * ms / n) if n else None}
     st = groups[0]
 
+    # The same kernel launched once for all layers (one context, one stream): its duration at the
+    # full 28-layer shape, for comparison with the per-group launches above.  The cache contents
+    # are the groups' current ones, the inputs the timed chunks.
+    full = None
+    if NS > 1 and not args.no_full_launch:
+        fs = DecodeState.from_workload(wl, device=dev, params=params)
+        for name in ("K", "V", "pos", "F_hist"):
+            getattr(fs, name).copy_(torch.cat([getattr(g_, name) for g_ in groups], dim=0))
+        fs.qwin.copy_(torch.cat([g_.qwin for g_ in groups], dim=1))
+        fs.d_state.copy_(torch.cat([g_.d_state for g_ in groups], dim=0))
+        fs.len_host = host["len"]
+        fs.ctx.profile_enable(True)
+        t_f = t_abs + K
+        for ci, chunk in enumerate(chunks[:4]):
+            qf, kf, vf = [torch.cat([chunk[g][i] for g in range(NS)], dim=1).contiguous() for i in range(3)]
+            for i in range(s):
+                fs.attend_decode(qf[i], kf[i], vf[i], t_f)
+                if fs.is_trigger(t_f):
+                    fs.evict(t_f)
+                t_f += 1
+        torch.cuda.synchronize()
+        ms, n = fs.ctx.profile_read("attend")
+        fs.ctx.profile_enable(False)
+        us = 1e3 * ms / n
+        full = {"launches": n, "avg_launch_us": us, "algorithmic_bytes_per_launch": algorithmic_bytes(wl)["attend"],
+                "achieved": algorithmic_bytes(wl)["attend"] / (us * 1e-6) / 1e9,
+                "frac": algorithmic_bytes(wl)["attend"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "unit": "GB/s"}
+        del fs
+
     # read bandwidth a trivial streaming kernel sustains on this GPU, for context: over a buffer
     # far larger than any cache, and over one the size of this workload's K+V cache
     from paper_2512_00504_amd.binding import probe_stream_read
@@ -370,6 +401,7 @@ def main():
                      "launches_per_step": NS,
                      "note": "launch durations from HIP events with the launches serialised on one stream; "
                              "the timed region overlaps the groups' launches on separate streams"},
+        "roofline_all_layers_one_launch": full,
         "cpu_baseline": cpu,
         "whole_step": {"algorithmic_bytes_per_step": bytes_per_step,
                        "GBps": bytes_per_step * K / elapsed / 1e9,
