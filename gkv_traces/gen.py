@@ -80,14 +80,16 @@ class Trace:
         return self._static[layer]
 
     # ---- one block of 64 steps for one (layer, sequence) ------------------
-    def _block(self, layer: int, seq: int, block: int):
+    def _block(self, layer: int, seq: int, block: int, need_q: bool = True):
+        """need_q=False skips drawing the queries (q comes back as None); every stream has its own
+        generator, so k and v are the same values either way."""
         cfg = self.cfg
         hq, hkv, d, grp = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.group
         t = np.arange(block * BLOCK, (block + 1) * BLOCK)
         gq = _rng(cfg.seed, _KIND_Q, layer, seq, block)
         gk = _rng(cfg.seed, _KIND_K, layer, seq, block)
         gv = _rng(cfg.seed, _KIND_V, layer, seq, block)
-        q = gq.standard_normal((BLOCK, hq, d), dtype=np.float32)
+        q = gq.standard_normal((BLOCK, hq, d), dtype=np.float32) if need_q else None
         v = gv.standard_normal((BLOCK, hkv, d), dtype=np.float32)
         if cfg.recipe == "heavy_tail":
             k = gk.standard_t(3.0, size=(BLOCK, hkv, d)).astype(np.float32)
@@ -103,33 +105,38 @@ class Trace:
             boosted = gk.random(BLOCK) < BOOST_RATE
             k[boosted] += self.boost * u[None, :, :]
             burst = ((t - BURST_START) % BURST_PERIOD) < BURST_LEN
-            uq = np.repeat(u, grp, axis=0)              # [h_q, d]: head i -> group i // grp
-            q[burst] += self.boost * uq[None, :, :]
+            if need_q:
+                uq = np.repeat(u, grp, axis=0)          # [h_q, d]: head i -> group i // grp
+                q[burst] += self.boost * uq[None, :, :]
         elif cfg.recipe != "heavy_tail":
             raise ValueError(cfg.recipe)
         if cfg.dtype == "bf16":
-            q, k, v = bf16_round(q), bf16_round(k), bf16_round(v)
+            q, k, v = (bf16_round(q) if need_q else None), bf16_round(k), bf16_round(v)
         return q, k, v
 
-    def unit_steps(self, layer: int, seq: int, t0: int, n: int):
-        """q [n,h_q,d], k [n,h_kv,d], v [n,h_kv,d] (float32, dtype-rounded) for steps t0..t0+n-1."""
+    def unit_steps(self, layer: int, seq: int, t0: int, n: int, need_q: bool = True):
+        """q [n,h_q,d], k [n,h_kv,d], v [n,h_kv,d] (float32, dtype-rounded) for steps t0..t0+n-1
+        (q is None with need_q=False)."""
         out_q, out_k, out_v = [], [], []
         blk0, blk1 = t0 // BLOCK, (t0 + n - 1) // BLOCK
         for blk in range(blk0, blk1 + 1):
-            q, k, v = self._block(layer, seq, blk)
+            q, k, v = self._block(layer, seq, blk, need_q)
             lo = max(t0, blk * BLOCK) - blk * BLOCK
             hi = min(t0 + n, (blk + 1) * BLOCK) - blk * BLOCK
-            out_q.append(q[lo:hi]); out_k.append(k[lo:hi]); out_v.append(v[lo:hi])
-        return (np.concatenate(out_q), np.concatenate(out_k), np.concatenate(out_v))
+            if need_q:
+                out_q.append(q[lo:hi])
+            out_k.append(k[lo:hi]); out_v.append(v[lo:hi])
+        return (np.concatenate(out_q) if need_q else None, np.concatenate(out_k), np.concatenate(out_v))
 
-    def batch_steps(self, t0: int, n: int, layers=None, seqs=None, workers: int = 1):
+    def batch_steps(self, t0: int, n: int, layers=None, seqs=None, workers: int = 1, need_q: bool = True):
         """q [n,L,B,h_q,d], k/v [n,L,B,h_kv,d] (float32, dtype-rounded) for the whole batch.
-        `workers` > 1 draws the (layer, sequence) pairs on a thread pool (same values)."""
+        `workers` > 1 draws the (layer, sequence) pairs on a thread pool (same values);
+        need_q=False returns q = None (a prompt needs keys and values only)."""
         cfg = self.cfg
         layers = range(cfg.n_layers) if layers is None else layers
         seqs = range(cfg.batch) if seqs is None else seqs
         L, B = len(layers), len(seqs)
-        q = np.empty((n, L, B, cfg.n_q_heads, cfg.head_dim), np.float32)
+        q = np.empty((n, L, B, cfg.n_q_heads, cfg.head_dim), np.float32) if need_q else None
         k = np.empty((n, L, B, cfg.n_kv_heads, cfg.head_dim), np.float32)
         v = np.empty_like(k)
         for layer in layers:
@@ -137,7 +144,9 @@ class Trace:
 
         def fill(args):
             li, layer, bi, seq = args
-            q[:, li, bi], k[:, li, bi], v[:, li, bi] = self.unit_steps(layer, seq, t0, n)
+            qq, k[:, li, bi], v[:, li, bi] = self.unit_steps(layer, seq, t0, n, need_q)
+            if need_q:
+                q[:, li, bi] = qq
 
         jobs = [(li, layer, bi, seq) for li, layer in enumerate(layers) for bi, seq in enumerate(seqs)]
         if workers > 1:

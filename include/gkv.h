@@ -50,7 +50,12 @@
  *     host before anything is enqueued, a failed call enqueues nothing.
  *     Results are deterministic: same inputs, same bits.
  *   - A compression call is a no-op for every (layer, sequence) whose length is
- *     not above the budget, so ragged batches are legal.
+ *     not above the budget, so ragged batches are legal.  It is also a no-op while
+ *     fewer than w steps have been decoded since LEN_STEP (the observation window
+ *     consists of generated tokens: a prompt loaded as {prompt_len, first_step, 0, 0}
+ *     brings keys and values but no window queries, so the ring slots are not yet
+ *     all written).  In a batch every sequence shares the step counter; a sequence
+ *     with a shorter prompt simply starts with a shorter cache.
  */
 #ifndef GKV_H
 #define GKV_H
@@ -66,7 +71,7 @@ typedef enum {
   GKV_OK = 0,
   GKV_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, alpha outside [0,1], w > s, w >= b ... */
   GKV_ERR_SHAPE = 2,         /* shape the kernels do not support (see gkv_create) */
-  GKV_ERR_WORKSPACE = 3,     /* workspace pointer missing */
+  GKV_ERR_WORKSPACE = 3,     /* workspace pointer missing, or sized for fewer attend_splits */
   GKV_ERR_HIP = 4,           /* a HIP runtime call failed */
   GKV_ERR_UNSUPPORTED = 5,
   GKV_ERR_OVERFLOW = 6       /* len_max_host would exceed the capacity */
@@ -82,7 +87,9 @@ typedef struct gkv_config {
   int32_t n_q_heads, n_kv_heads;    /* h_q, h_kv; h_q % h_kv == 0 */
   int32_t head_dim;                 /* d; multiple of 16/sizeof(element), at most 1024 bytes per row */
   int32_t budget, window, interval; /* b, w, s;  w <= s, w < b */
-  int32_t capacity;                 /* rows per KV head; >= b + s, multiple of 32, at most 4096 */
+  int32_t capacity;                 /* rows per KV head; >= b + s, multiple of 32, at most 4096 and small
+                                       enough for every kernel's 64 KiB of LDS: 16*(capacity+1+d) bytes
+                                       (plain attend kernel) and 16*capacity+32 (redundancy score) */
   int32_t dtype;                    /* gkv_dtype */
   int32_t combine;                  /* gkv_combine */
   float alpha;                      /* memory-decay rate in [0,1]; 0 = local score only */
@@ -98,8 +105,10 @@ gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx);
 void gkv_destroy(gkv_ctx* ctx);
 const char* gkv_status_string(gkv_status st);
 
-/* Bytes of device workspace the calls below need for this context. */
-gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes);
+/* Bytes of device workspace the calls below need for this context with the tuning knobs as they
+ * are now; the context remembers the "attend_splits" value the size covers, and
+ * gkv_attend_decode returns GKV_ERR_WORKSPACE if the knob was raised afterwards. */
+gkv_status gkv_workspace_bytes(gkv_ctx* ctx, size_t* out_bytes);
 /* Enqueues a fill kernel that zeroes the workspace's counters (used only when one
  * unit's attention is split over several workgroups).  Call once. */
 gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream);
@@ -115,7 +124,7 @@ gkv_status gkv_cache_bytes(const gkv_config* cfg, int32_t rows, int32_t score_el
 int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_t n_tiled);
 
 /* Tuning knobs (host only): "attend_splits" (workgroups per unit in the matrix-core
- * attend kernel; 0 = default = 1; set before gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
+ * attend kernel; 0 = default = 1; set it before gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
  * the matrix-core attend kernel), "force_generic" (1 = use the plain vector-ALU
  * kernels even where matrix-core kernels exist). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);

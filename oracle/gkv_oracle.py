@@ -18,7 +18,12 @@ Readings taken where the paper is silent (each is a switch or a comment here):
     are the candidates, of which b-w are kept;
   * max_j in the normalisation runs over the candidates (`norm_over="all"`
     takes it over all l columns instead);
-  * compression runs after step t when (t+1) % s == 0 and l > b;
+  * compression runs after step t when (t+1) % s == 0 and l > b, and only once w queries
+    have been decoded since the cache was loaded (the observation window consists of
+    generated tokens; a prompt brings keys and values but no window queries);
+  * a prompt is P rows appended before decoding starts; in a batch every sequence shares the
+    step counter, so a sequence with a shorter prompt simply starts with a shorter cache
+    (its prompt occupies the positions just before the first decode step);
   * at the first compression there is no history (n_hist = 0) and the
     recorded history is the normalised score of the kept entries;
   * kept entries are stored in ascending original position, then the window;
@@ -158,7 +163,7 @@ def pool_scores(F, kernel):
     return out
 
 
-def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, fp32_decisions=False, return_margin=False):
+def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, return_margin=False, return_parts=False):
     """Redundancy score R [h_kv, l] of the cached keys (appendix "Integrating the Global Score
     with Other Methods"): keys normalised to K/(||K||_2 + eps), cosine-similarity matrix C,
     entries below the threshold tau set to zero as well as those of the most recent tokens,
@@ -168,30 +173,23 @@ def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, fp32_decisions=Fa
     kept when C >= tau; the diagonal (a key with itself) is zeroed; "most recent tokens" zeroes
     the columns of the last n_recent rows, so those tokens collect no redundancy.
 
-    The threshold turns a real number into a yes/no.  With fp32_decisions the cosine that is
-    compared and summed is formed the way an fp32 device forms it - fp32(dot) times fp32
-    reciprocal norms, fp32 products - so that both sides take that decision in the same
-    precision; everything else stays fp64.  return_margin adds, per head, the smallest
-    |C - tau| over the entries that count (how robust the decisions were).
+    return_margin adds, per head, the smallest |C - tau| over the entries that count (how far
+    the yes/no decisions were from the threshold).  return_parts adds the intermediates
+    dict(C=[h_kv,l,l] cosines, col=[h_kv,l] column sums) so that a checker can see which
+    entries sit on the threshold.
     """
     K = np.asarray(K, np.float64)
     l = int(length)
-    R = np.zeros((K.shape[0], l))
-    margin = np.full(K.shape[0], np.inf)
-    for j in range(K.shape[0]):
+    h = K.shape[0]
+    R = np.zeros((h, l))
+    margin = np.full(h, np.inf)
+    C_all = np.zeros((h, l, l))
+    col_all = np.zeros((h, l))
+    for j in range(h):
         Kj = K[j, :l]
-        if fp32_decisions:
-            f32 = np.float32
-            ss = (Kj * Kj).sum(axis=1).astype(f32)
-            inv = f32(1.0) / (np.sqrt(ss) + f32(eps))
-            C = ((Kj @ Kj.T).astype(f32) * inv[:, None]) * inv[None, :]
-            keep = C >= f32(tau)
-            C = C.astype(np.float64)
-        else:
-            Kn = Kj / (np.linalg.norm(Kj, axis=1, keepdims=True) + eps)
-            C = Kn @ Kn.T
-            keep = C >= tau
-        Cm = np.where(keep, C, 0.0)
+        Kn = Kj / (np.linalg.norm(Kj, axis=1, keepdims=True) + eps)
+        C = Kn @ Kn.T
+        Cm = np.where(C >= tau, C, 0.0)
         np.fill_diagonal(Cm, 0.0)
         if n_recent > 0:
             Cm[:, l - n_recent:] = 0.0
@@ -199,7 +197,13 @@ def redundancy_score(K, length, tau=0.5, n_recent=0, eps=1e-8, fp32_decisions=Fa
         R[j] = softmax(col)
         off = np.abs(C - tau) + np.eye(l) * 10.0
         margin[j] = off[:, :l - n_recent].min() if l > n_recent else np.inf
-    return (R, margin) if return_margin else R
+        C_all[j], col_all[j] = C, col
+    out = (R,)
+    if return_margin:
+        out += (margin,)
+    if return_parts:
+        out += (dict(C=C_all, col=col_all),)
+    return out if len(out) > 1 else R
 
 
 def combine_redundancy(F, R, lam, n_cand=None):
@@ -248,11 +252,24 @@ class OracleA:
         self.q_recent.append(np.asarray(q, np.float64))
         self.q_recent = self.q_recent[-self.w:]
 
+    def prefill(self, t_first, k, v):
+        """Prompt of P tokens (k, v [P, h_kv, d]) at positions t_first .. t_first+P-1: rows are
+        appended, nothing attends and no window query is recorded."""
+        k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
+        for i in range(k.shape[0]):
+            n = self.len
+            self.K[:, n] = k[i]; self.V[:, n] = v[i]; self.pos[:, n] = t_first + i
+            self.len = n + 1
+
+    def is_trigger(self, t):
+        """After step t: every s steps, once the cache exceeds the budget and the window is full."""
+        return (t + 1) % self.s == 0 and self.len > self.b and len(self.q_recent) >= self.w
+
     def step(self, t, q, k, v):
         """Append (k, v), attend with q, then compress if this step is a trigger."""
         self.append(t, q, k, v)
         o = attend(q, self.K, self.V, self.len, self.scale)
-        if (t + 1) % self.s == 0 and self.len > self.b:
+        if self.is_trigger(t):
             self.compress()
         return o
 
@@ -278,11 +295,11 @@ class OracleA:
             keep = select_topk(F, b - w)
         else:
             rp = self.redundancy
-            R, margin = redundancy_score(self.K, l, rp["tau"], rp["n_recent"], rp.get("eps", 1e-8),
-                                         fp32_decisions=rp.get("fp32_decisions", False), return_margin=True)
+            R, margin, parts = redundancy_score(self.K, l, rp["tau"], rp["n_recent"], rp.get("eps", 1e-8),
+                                                return_margin=True, return_parts=True)
             Fsel = combine_redundancy(F, R, rp["lam"], n_cand=c)
             keep = select_topk(Fsel, b - w)
-            ev.update(R=R, Fsel=Fsel, tau_margin=margin)
+            ev.update(R=R, Fsel=Fsel, tau_margin=margin, C=parts["C"], col=parts["col"])
         ev["keep"] = keep.copy()
         # eviction log: original positions of the candidates that are dropped (Section 5)
         ev["evicted_pos"] = [sorted(set(self.pos[j, :c].tolist()) - set(self.pos[j, keep[j]].tolist()))
@@ -317,7 +334,7 @@ class OracleB:
         self.b, self.w, self.s = budget, window, interval
         self.alpha, self.form = alpha, form
         self.scale = 1.0 / np.sqrt(d) if scale is None else scale
-        self.q_all, self.k_all, self.v_all = [], [], []
+        self.q_all, self.k_all, self.v_all = {}, {}, {}  # position -> vectors (prompt positions have no q)
         self.alive = [set() for _ in range(h_kv)]
         self.hist = [dict() for _ in range(h_kv)]       # position -> recorded global score
         self.kept_log = []                              # per event: per head sorted kept positions
@@ -326,9 +343,16 @@ class OracleB:
         z = np.array([np.dot(self.k_all[p][j], q_vec) for p in positions]) * self.scale
         return softmax(z)
 
+    def prefill(self, t_first, k, v):
+        for i in range(len(k)):
+            p = t_first + i
+            self.k_all[p] = np.asarray(k[i], np.float64); self.v_all[p] = np.asarray(v[i], np.float64)
+            for j in range(self.h_kv):
+                self.alive[j].add(p)
+
     def step(self, t, q, k, v):
         q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
-        self.q_all.append(q); self.k_all.append(k); self.v_all.append(v)
+        self.q_all[t] = q; self.k_all[t] = k; self.v_all[t] = v
         o = np.zeros((self.h_q, self.d))
         for j in range(self.h_kv):
             self.alive[j].add(t)
@@ -337,7 +361,8 @@ class OracleB:
                 p = self._probs(q[i], j, positions)
                 for pn, n in zip(p, positions):
                     o[i] += pn * self.v_all[n][j]
-        if (t + 1) % self.s == 0 and len(self.alive[0]) > self.b:
+        win = range(t - self.w + 1, t + 1)
+        if (t + 1) % self.s == 0 and len(self.alive[0]) > self.b and all(p in self.q_all for p in win):
             self._compress(t)
         return o
 

@@ -36,8 +36,8 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
   __shared__ float red[8];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const SeqState st = load_state(d_state, lb);
-  const int l = length_before_step(st, step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(st, step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const int c = l - dm.w;
   int n_hist = st.n_hist;
   n_hist = n_hist < 0 ? 0 : (n_hist > c ? c : n_hist);
@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const floa
   __shared__ int tmp[4];
   __shared__ int sel[2];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const int c = l - dm.w;
   const int k = dm.b - dm.w;                   // c > k because l > b
   const float* Fu = F + (size_t)unit * dm.cap;
@@ -141,8 +141,8 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const bool isK = blockIdx.y == 0;
   const SeqState st = load_state(d_state, lb);
-  const int l = length_before_step(st, step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(st, step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const int c = l - dm.w, k = dm.b - dm.w, b = dm.b;
   const int nt_old = st.n_tiled, nt_new = b & ~15;
   const int32_t* Ku = keep_idx + (size_t)unit * k;
@@ -214,8 +214,8 @@ __global__ __launch_bounds__(256) void pool_scores_kernel(GkvDims dm, const floa
                                                           int kernel, float* __restrict__ F_out) {
   extern __shared__ float fbuf[];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const int c = l - dm.w, half = kernel / 2;
   const float* Fu = F + (size_t)unit * dm.cap;
   for (int n = tid; n < c; n += 256) fbuf[n] = Fu[n];
@@ -239,8 +239,8 @@ __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, cons
   __shared__ int tmp[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   int32_t* Eu = evicted + (size_t)unit * dm.s;
-  const int l = length_before_step(load_state(d_state, lb), step + 1, dm.cap);
-  if (l <= dm.b) {
+  const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
+  if (l == 0) {
     for (int i = tid; i < dm.s; i += 256) Eu[i] = -1;
     return;
   }
@@ -270,8 +270,8 @@ __global__ void finalize_state_kernel(GkvDims dm, int32_t* d_state, int step) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= dm.L * dm.B) return;
   const SeqState st = load_state(d_state, i);
-  const int l = length_before_step(st, step + 1, dm.cap);
-  if (l > dm.b) *(int4*)(d_state + 4 * (size_t)i) = make_int4(dm.b, step + 1, dm.b - dm.w, dm.b & ~15);
+  const int l = compression_length(st, step, dm.b, dm.w, dm.cap);
+  if (l > 0) *(int4*)(d_state + 4 * (size_t)i) = make_int4(dm.b, step + 1, dm.b - dm.w, dm.b & ~15);
 }
 
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {

@@ -59,7 +59,25 @@ static gkv_status validate_config(const gkv_config* c) {
     return GKV_ERR_SHAPE;
   const int64_t units = (int64_t)c->n_layers * c->batch * c->n_kv_heads;
   if (units > (1 << 24)) return GKV_ERR_SHAPE;
+  if (gkv_max_lds_bytes(c) > GKV_LDS_LIMIT) return GKV_ERR_SHAPE;
   return GKV_OK;
+}
+
+// Largest LDS footprint (dynamic + static, bytes) of any kernel that can be selected for this
+// configuration; the plain vector-ALU kernels are included because "force_generic" may select them
+// for any shape.  A workgroup gets 64 KiB without opting in to more.
+size_t gkv_max_lds_bytes(const gkv_config* c) {
+  const size_t cap = (size_t)c->capacity, d = (size_t)c->head_dim;
+  const size_t g = (size_t)(c->n_q_heads / c->n_kv_heads);
+  size_t need = 16 * (cap + 1 + d);                                 // attend_generic: 4 wavefronts x float[cap + 1 + d]
+  auto upd = [&](size_t x) { if (x > need) need = x; };
+  upd(4 * (3 * cap + d));                                           // score_generic: at least one wavefront's float[3 cap + d]
+  upd(4 * cap + 1024 + 64);                                         // select_topk: keys[cap] + histogram + scan scratch
+  upd(16 * cap + 32);                                               // redundancy: double cs[cap], red[4], inv[cap]
+  upd(4 * cap + 64);                                                // pooled score / eviction log
+  if (c->dtype == GKV_BF16 && d == 128 && g <= 16)
+    upd(4 * (4 * g * 132 + 128) + (32 + 16 * g) * 16 + 16);         // attend_mfma: partial outputs + staged rows
+  return need;
 }
 
 extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
@@ -78,6 +96,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   d.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : (float)(1.0 / sqrt((double)cfg->head_dim));
   c->esz = cfg->dtype == GKV_F32 ? 4 : 2;
   c->attend_splits = 0;
+  c->ws_splits = 1;
   c->attend_tile = 16;
   c->force_generic = 0;
   c->mfma_ok = cfg->dtype == GKV_BF16 && d.d == 128 && d.g <= 16;
@@ -125,14 +144,11 @@ int gkv_effective_splits(const gkv_ctx* ctx) {
   return s > m ? m : s;
 }
 
-static size_t ws_partials_bytes(const gkv_ctx* ctx) {
-  // sized for the largest split count so that "attend_splits" can change without reallocation
-  const bool mfma = ctx->mfma_ok;
-  if (!mfma) return 0;
+// Split-K partials for `splits` workgroups per unit (none when a unit is not split).
+static size_t ws_partials_bytes(const gkv_ctx* ctx, int splits) {
+  if (!ctx->mfma_ok || splits <= 1) return 0;
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
-  int s = ctx->attend_splits > 0 ? ctx->attend_splits : gkv_effective_splits(ctx);
-  if (s > max_splits(ctx)) s = max_splits(ctx);
-  return s > 1 ? units * s * ctx->dims.g * (ctx->dims.d + 2) * sizeof(float) : 0;
+  return units * splits * ctx->dims.g * (ctx->dims.d + 2) * sizeof(float);
 }
 
 GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
@@ -144,10 +160,12 @@ GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
   return w;
 }
 
-extern "C" gkv_status gkv_workspace_bytes(const gkv_ctx* ctx, size_t* out_bytes) {
+extern "C" gkv_status gkv_workspace_bytes(gkv_ctx* ctx, size_t* out_bytes) {
   if (!ctx || !out_bytes) return GKV_ERR_INVALID_ARG;
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
-  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx)) + 256;
+  // the workspace is sized for the split count in force now; the decode call refuses a larger one
+  ctx->ws_splits = gkv_effective_splits(ctx);
+  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx, ctx->ws_splits)) + 256;
   return GKV_OK;
 }
 
@@ -227,6 +245,7 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   GkvLaunch ln{ctx, GKV_K_ATTEND, (hipStream_t)stream};
   if (use_mfma_attend(ctx)) {
     a.splits = gkv_effective_splits(ctx);
+    if (a.splits > ctx->ws_splits) return GKV_ERR_WORKSPACE;   // partials would not fit the workspace as sized
     return hip_status(gkv_launch_attend_mfma(ln, ctx->dims, a));
   }
   return hip_status(gkv_launch_attend_generic(ln, ctx->dims, ctx->cfg.dtype, a));

@@ -22,6 +22,7 @@ struct gkv_ctx {
   GkvDims dims;
   int32_t esz;            // bytes per element
   int32_t attend_splits;  // 0 = automatic
+  int32_t ws_splits;      // split count the workspace was sized for by gkv_workspace_bytes (1 = no partials)
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
   bool mfma_ok;           // bf16, d == 128, g <= 16
@@ -38,6 +39,8 @@ struct GkvWorkspace {
 
 static inline size_t gkv_align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+constexpr size_t GKV_LDS_LIMIT = 65536;
+size_t gkv_max_lds_bytes(const gkv_config* cfg);
 int gkv_effective_splits(const gkv_ctx* ctx);
 GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base);
 
@@ -118,6 +121,15 @@ __device__ __forceinline__ SeqState load_state(const int32_t* d_state, int lb) {
 __device__ __forceinline__ int length_before_step(const SeqState& s, int t, int cap) {
   const int l = s.len + (t - s.len_step);
   return l < 0 ? 0 : (l > cap ? cap : l);
+}
+
+// Whether the compression after decode step `step` applies to this (layer, sequence): its cache
+// must exceed the budget, and the observation window must consist of generated tokens, i.e. at
+// least w steps were decoded since the cache was loaded or last compacted (a prompt brings keys
+// and values but no window queries).  Returns the length l the compression sees, or 0 for "skip".
+__device__ __forceinline__ int compression_length(const SeqState& s, int step, int b, int w, int cap) {
+  const int l = length_before_step(s, step + 1, cap);
+  return (l > b && step + 1 - s.len_step >= w) ? l : 0;
 }
 
 // Element offset of (row n, channel c) in one KV head's K block whose first n_tiled rows are in

@@ -19,9 +19,12 @@ struct RedArgs {
   float lambda, tau, eps; int32_t n_recent; float* R_norm; float* F_sel;
 };
 
-// Column sums reach the hundreds while the decision they feed is taken at 1e-6, so they are
-// accumulated and kept in fp64 (each term is an fp32 product); the exponent cs - max is formed
-// in fp64 and only then rounded.
+// Precision.  A column sum adds up to l cosines and reaches the hundreds, R' = exp(col - max col)
+// is compared at 1e-5 relative, and the threshold turns each cosine into a yes/no.  So the
+// reciprocal norms are formed in fp64 (a per-row fp32 rounding would be a systematic error of
+// col_j * 1e-7 in every column), each cosine is the dot product (fp32 accumulation of exact
+// bf16 products on the matrix cores, fp64 in the plain kernel) times the two fp64 reciprocal
+// norms, the threshold compares that fp64 value, the column sums and exp(col - max) are fp64.
 __device__ __forceinline__ double block_max_f64(double v, double* red) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
@@ -43,14 +46,14 @@ __device__ __forceinline__ void finish_unit(const GkvDims& dm, const RedArgs& a,
   const float* Fu = a.F + (size_t)unit * dm.cap;
   const int c = l - dm.w;
   for (int j = tid; j < l; j += 256) {
-    const float rn = expf((float)(cs[j] - mx));
+    const float rn = (float)exp(cs[j] - mx);
     Ru[j] = rn;
     if (j < c) Fs[j] = a.lambda * Fu[j] - (1.f - a.lambda) * rn;
   }
 }
 
 // ---- any dtype / shape ------------------------------------------------------------------------
-// Dynamic LDS: double cs[cap]; double red[4]; float inv[cap]
+// Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
 template <typename T>
 __global__ __launch_bounds__(256) void redundancy_generic_kernel(GkvDims dm, RedArgs a) {
   extern __shared__ double smem[];
@@ -58,18 +61,18 @@ __global__ __launch_bounds__(256) void redundancy_generic_kernel(GkvDims dm, Red
   const int tid = threadIdx.x, unit = blockIdx.x, lb = unit / dm.Hkv, d = dm.d;
   double* cs = (double*)smem;
   double* red = cs + dm.cap;
-  float* inv = (float*)(red + 4);
+  double* inv = red + 4;
   const SeqState st = load_state(a.d_state, lb);
-  const int l = length_before_step(st, a.step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(st, a.step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const T* Kh = (const T*)a.K + (size_t)unit * dm.cap * d;
   for (int n = tid; n < l; n += 256) {
-    float ss = 0.f;
+    double ss = 0.0;
     for (int ch = 0; ch < d; ++ch) {
-      const float x = Elem<T>::ld(Kh + k_elem_offset<EPC>(n, ch, d, st.n_tiled));
-      ss = fmaf(x, x, ss);
+      const double x = (double)Elem<T>::ld(Kh + k_elem_offset<EPC>(n, ch, d, st.n_tiled));
+      ss = fma(x, x, ss);
     }
-    inv[n] = 1.f / (sqrtf(ss) + a.eps);
+    inv[n] = 1.0 / (sqrt(ss) + (double)a.eps);
   }
   __syncthreads();
   const int first_recent = l - a.n_recent;
@@ -78,12 +81,12 @@ __global__ __launch_bounds__(256) void redundancy_generic_kernel(GkvDims dm, Red
     if (j < first_recent) {
       for (int k = 0; k < l; ++k) {
         if (k == j) continue;
-        float dot = 0.f;
+        double dot = 0.0;
         for (int ch = 0; ch < d; ++ch)
-          dot = fmaf(Elem<T>::ld(Kh + k_elem_offset<EPC>(k, ch, d, st.n_tiled)),
-                     Elem<T>::ld(Kh + k_elem_offset<EPC>(j, ch, d, st.n_tiled)), dot);
-        const float cv = dot * inv[k] * inv[j];
-        if (cv >= a.tau) col += (double)cv;
+          dot = fma((double)Elem<T>::ld(Kh + k_elem_offset<EPC>(k, ch, d, st.n_tiled)),
+                    (double)Elem<T>::ld(Kh + k_elem_offset<EPC>(j, ch, d, st.n_tiled)), dot);
+        const double cv = dot * inv[k] * inv[j];
+        if (cv >= (double)a.tau) col += cv;
       }
     }
     cs[j] = col;
@@ -108,23 +111,23 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
 // A wavefront owns column tiles J = wave, wave+4, ...; for each it walks all row tiles T.  The
 // A operand of a tile (lane = key + 16*kblock, 8 channels) is also a valid B operand, so
 // C[k, j] = sum_c mfma(A_T[c], A_J[c]) lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
-// Dynamic LDS: double cs[cap]; double red[4]; float inv[cap]
+// Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
 __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
   extern __shared__ double smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, kb = lane >> 4;
   const int unit = blockIdx.x, lb = unit / dm.Hkv;
   double* cs = (double*)smem;
   double* red = cs + dm.cap;
-  float* inv = (float*)(red + 4);
+  double* inv = red + 4;
   const SeqState st = load_state(a.d_state, lb);
-  const int l = length_before_step(st, a.step + 1, dm.cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(st, a.step, dm.b, dm.w, dm.cap);
+  if (l == 0) return;
   const char* Kh = (const char*)a.K + (size_t)unit * dm.cap * ROW_BYTES;
   const int n_tiles = (l + 15) >> 4;
 
   // row norms: a quarter-wave per row, 16 bytes per lane
   for (int n = tid >> 4; n < n_tiles * 16; n += 16) {
-    float ss = 0.f;
+    double ss = 0.0;
     if (n < l) {
       const int ch = tid & 15;
       const char* p = (n < st.n_tiled) ? Kh + (size_t)(n >> 4) * TILE_BYTES + ch * 256 + (n & 15) * 16
@@ -132,22 +135,23 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       const u32x4 v = *(const u32x4*)p;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xffff0000u);
-        ss = fmaf(lo, lo, ss);
-        ss = fmaf(hi, hi, ss);
+        const double lo = (double)__uint_as_float(v[i] << 16), hi = (double)__uint_as_float(v[i] & 0xffff0000u);
+        ss = fma(lo, lo, ss);
+        ss = fma(hi, hi, ss);
       }
     }
     ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4); ss += __shfl_xor(ss, 8);
-    if ((tid & 15) == 0) inv[n] = n < l ? 1.f / (sqrtf(ss) + a.eps) : 0.f;
+    if ((tid & 15) == 0) inv[n] = n < l ? 1.0 / (sqrt(ss) + (double)a.eps) : 0.0;
   }
   __syncthreads();
 
   // NC column tiles per wavefront pass, so that each row tile fetched (from L2) is used NC times
   constexpr int NC = 4;
   const int first_recent = l - a.n_recent;
+  const double tau = (double)a.tau;
   for (int J0 = wave * NC; J0 < n_tiles; J0 += 4 * NC) {
     u32x4 colA[NC][4];
-    float inv_j[NC];
+    double inv_j[NC];
     double col[NC];
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
@@ -160,7 +164,9 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       u32x4 rowA[4];
       load_k_tile(rowA, Kh, T, st.n_tiled, lane, r, kb);
       const int k0 = 16 * T + 4 * kb;
-      const f32x4 invk = *(const f32x4*)(inv + k0);      // rows >= l have inv = 0
+      double invk[4];                                    // rows >= l have inv = 0
+#pragma unroll
+      for (int e = 0; e < 4; ++e) invk[e] = inv[k0 + e];
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -171,8 +177,8 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
         const int j = 16 * (J0 + cc) + r;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float cv = acc[e] * invk[e] * inv_j[cc];
-          if (cv >= a.tau && k0 + e != j && k0 + e < l) col[cc] += (double)cv;
+          const double cv = (double)acc[e] * invk[e] * inv_j[cc];
+          if (cv >= tau && k0 + e != j && k0 + e < l) col[cc] += cv;
         }
       }
     }
@@ -196,7 +202,7 @@ hipError_t gkv_launch_redundancy(const GkvLaunch& ln, const GkvDims& dm, int dty
                                  float eps, int32_t n_recent, float* R_norm, float* F_sel) {
   RedArgs a{K, d_state, step, F, lambda, tau, eps, n_recent, R_norm, F_sel};
   const int units = dm.L * dm.B * dm.Hkv;
-  const size_t shmem = sizeof(double) * ((size_t)dm.cap + 4) + sizeof(float) * (size_t)dm.cap;
+  const size_t shmem = sizeof(double) * (2 * (size_t)dm.cap + 4);
   if (mfma) return gkv_launch(ln, redundancy_mfma_kernel, dim3(units), dim3(256), shmem, dm, a);
   if (dtype == GKV_F32)
     return gkv_launch(ln, redundancy_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);

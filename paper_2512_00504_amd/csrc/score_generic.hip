@@ -24,8 +24,8 @@ __global__ void score_generic_kernel(GkvDims dm, ScoreArgs a) {
   float* qs = sacc + cap;
 
   const SeqState st = load_state(a.d_state, lb);
-  const int l = length_before_step(st, a.step + 1, cap);
-  if (l <= dm.b) return;                     // not above the budget: no compression for this sequence
+  const int l = compression_length(st, a.step, dm.b, w, cap);
+  if (l == 0) return;                        // at or below the budget, or window not full: no compression
   const int c = l - w;
   const T* Kh = (const T*)a.K + (size_t)unit * cap * d;
 

@@ -71,8 +71,8 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   constexpr int ROWS = G * W;
 
   const SeqState seq = load_state(a.d_state, lb);
-  const int l = length_before_step(seq, a.step + 1, cap);
-  if (l <= dm.b) return;
+  const int l = compression_length(seq, a.step, dm.b, W, cap);
+  if (l == 0) return;
   const int cc = l - W;                     // number of candidates
 
   char* qs = smem_raw;

@@ -67,7 +67,10 @@ class DecodeState:
         self.out = z(L, B, Hq, d, dtype=dt)
         self.workspace = torch.zeros(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
         self.ctx.workspace_init(self.workspace)
-        self.len_host = 0          # host mirror of the (uniform) length, for launch sizing only
+        # host mirror of the device records, for launch sizing and the trigger only: per sequence,
+        # the cache length and the steps decoded since the cache was loaded or last compacted
+        self._len = [0] * B
+        self._since = [0] * B
 
     @classmethod
     def from_workload(cls, wl, device="cuda:0", params=None, **over):
@@ -76,6 +79,17 @@ class DecodeState:
                   capacity=wl.capacity, dtype=wl.dtype, combine=wl.combine, alpha=wl.alpha)
         kw.update(over)
         return cls(make_config(**kw), device=device, params=params)
+
+    @property
+    def len_host(self) -> int:
+        """Upper bound of every sequence's length, as the calls' len_max_host wants it."""
+        return max(self._len)
+
+    @len_host.setter
+    def len_host(self, value: int):
+        """Declare every sequence `value` rows long with a full observation window."""
+        self._len = [int(value)] * self.cfg.batch
+        self._since = [self.cfg.window] * self.cfg.batch
 
     # lengths as the kernels see them ---------------------------------------------------------
     def lengths(self, next_step: int) -> torch.Tensor:
@@ -88,7 +102,8 @@ class DecodeState:
         self.d_state[..., ST_LEN_STEP] = len_step
         self.d_state[..., ST_N_HIST] = n_hist
         self.d_state[..., ST_N_TILED] = n_tiled
-        self.len_host = int(length)
+        self._len = [int(length)] * self.cfg.batch
+        self._since = [0] * self.cfg.batch
 
     def load_prefix(self, k, v, t0=0):
         """Place tokens t0..t0+n-1 (k, v: [n, L, B, h_kv, d]) as cache rows 0..n-1 with positions
@@ -104,12 +119,45 @@ class DecodeState:
         self.pos[..., :n] = torch.arange(t0, t0 + n, dtype=torch.int32, device=self.device)
         self.set_state(n, t0 + n, 0, 0)
 
+    def load_prompt_rows(self, t_first, k, v, t0, prompt_lens):
+        """Place prompt tokens.  k, v [n, L, B, h_kv, d] hold positions t_first .. t_first+n-1 of
+        every sequence's token stream; sequence i's prompt is the positions [t0 - P_i, t0) (a
+        left-padded batch: decoding starts at step t0 for everyone) and goes to cache rows
+        [0, P_i), K row-major.  May be called chunk by chunk; finish with begin_decode().
+        Pure data placement."""
+        n = k.shape[0]
+        for i, P in enumerate(prompt_lens):
+            lo = max(t_first, t0 - P)
+            hi = min(t_first + n, t0)
+            if hi <= lo:
+                continue
+            r0 = lo - (t0 - P)
+            src = slice(lo - t_first, hi - t_first)
+            self.K[:, i, :, r0:r0 + hi - lo] = k[src, :, i].to(self.K.dtype).permute(1, 2, 0, 3)
+            self.V[:, i, :, r0:r0 + hi - lo] = v[src, :, i].to(self.V.dtype).permute(1, 2, 0, 3)
+            self.pos[:, i, :, r0:r0 + hi - lo] = torch.arange(lo, hi, dtype=torch.int32, device=self.device)
+
+    def begin_decode(self, t0, prompt_lens):
+        """Records {P_i, t0, 0, 0}: sequence i holds P_i prompt rows before decode step t0."""
+        rec = torch.tensor([[P, t0, 0, 0] for P in prompt_lens], dtype=torch.int32)
+        self.d_state.copy_(rec.to(self.device).expand(self.cfg.n_layers, -1, -1))
+        self._len = [int(P) for P in prompt_lens]
+        self._since = [0] * self.cfg.batch
+
+    def _after_compression(self):
+        """Host mirror of what the compression kernels decide per sequence."""
+        b, w = self.cfg.budget, self.cfg.window
+        for i in range(self.cfg.batch):
+            if self._len[i] > b and self._since[i] >= w:
+                self._len[i], self._since[i] = b, 0
+
     # one call each -------------------------------------------------------------------------
     def attend_decode(self, q, k_new, v_new, step):
         self.ctx.attend_decode(q, k_new, v_new, self.K, self.V, self.pos, step, self.qwin, self.d_state,
                                self.len_host, self.out, self.workspace)
         if k_new is not None:
-            self.len_host += 1
+            self._len = [x + 1 for x in self._len]
+        self._since = [x + 1 for x in self._since]
         return self.out
 
     def score_window(self, step):
@@ -133,15 +181,16 @@ class DecodeState:
     def compact(self, step):
         self.ctx.compact(self.keep_idx, self.F, self.K, self.V, self.F_hist, self.pos, self.d_state, step,
                          self.workspace)
-        if self.len_host > self.cfg.budget:
-            self.len_host = self.cfg.budget
+        self._after_compression()
 
     def evict(self, step):
         self.ctx.evict(self.qwin, self.K, self.V, self.F_hist, self.pos, self.d_state, step,
                        self.len_host, self.S, self.F, self.keep_idx, self.workspace)
-        if self.len_host > self.cfg.budget:
-            self.len_host = self.cfg.budget
+        self._after_compression()
 
     def is_trigger(self, step) -> bool:
-        """Host-side trigger: compression after every s generated tokens once above the budget."""
-        return (step + 1) % self.cfg.interval == 0 and self.len_host > self.cfg.budget
+        """Host-side trigger: compression after every s generated tokens, if some sequence is above
+        the budget with a full observation window (the kernels skip the others)."""
+        b, w = self.cfg.budget, self.cfg.window
+        return (step + 1) % self.cfg.interval == 0 and any(
+            n > b and k >= w for n, k in zip(self._len, self._since))

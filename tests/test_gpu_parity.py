@@ -112,6 +112,57 @@ def test_cfg3_full_size_longer_run():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+# The launch configurations the benchmark times, whole: every unit runs on the GPU, the oracle
+# follows a seeded sample of (layer, sequence) pairs that covers the first and last layer and
+# sequence.  The first b tokens are placed in the cache as a prompt (no compression can happen
+# before the cache exceeds the budget), then two whole compression cycles are decoded and every
+# step's output of the sampled pairs is compared.
+CFG4_PAIRS = [(0, 0), (0, 15), (27, 0), (27, 15), (13, 7), (5, 3), (20, 11), (9, 14)]
+CFG5_PAIRS = [(0, 0), (0, 63), (35, 0), (35, 63), (17, 31), (8, 50), (26, 5), (30, 40)]
+
+
+@pytest.mark.parametrize("name", ["cfg4_b512", "cfg4_b1024", "cfg4_b2048", "cfg4_b512_local"])
+def test_cfg4_full_launch_sampled_pairs(name):
+    wl = CONFIGS[name]
+    _say(f"{name}: 28 layers x 16 sequences = {wl.n_units} units, prompt {wl.budget}, 2 cycles, 8 sampled pairs")
+    st = run_parity(wl, 2 * wl.interval, pairs=CFG4_PAIRS, prompts=[wl.budget] * wl.batch,
+                    check_state_every_event=True, workers=16)
+    assert st["events"] == 2 and st["pair_events"] == 16
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+def test_cfg5_full_launch_sampled_pairs():
+    wl = CONFIGS["cfg5_large_batch"]
+    _say(f"cfg5: 36 layers x 64 sequences = {wl.n_units} units, prompt {wl.budget}, 2 cycles, 8 sampled pairs")
+    st = run_parity(wl, 2 * wl.interval, pairs=CFG5_PAIRS, prompts=[wl.budget] * wl.batch, chunk=64,
+                    check_state_every_event=True, workers=16)
+    assert st["events"] == 2 and st["pair_events"] == 16
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
+# ------------------------------------------------------------------ prompts, ragged batches
+def test_ragged_prompts_small_shape():
+    # b = 96, w = 16, s = 32: prompts of 0, 37 and 150 rows (one longer than the budget), decoding
+    # starts at step 150 for all; every compression sees a different length per sequence, and the
+    # long prompt has to wait for a full window before its first compression
+    wl = CONFIGS["cfg2_single_layer"].with_(n_layers=2, batch=3, n_q_heads=8, n_kv_heads=2, budget=96, window=16,
+                                            interval=32, seed=31)
+    st = run_parity(wl, 200, prompts=[0, 37, 150], chunk=64, cfg_over=dict(capacity=192))
+    lens = sorted({ev["len"] for orc in st["oracles"].values() for ev in orc.events})
+    _say(f"  lengths seen by compressions: {lens}")
+    assert len(lens) >= 4 and st["pair_events"] >= 20
+
+
+def test_ragged_prompts_cfg3_shape():
+    # P = 0, 37, 300 at the 28q/4kv x 128 head shape (matrix-core kernels): at the trigger after
+    # step 895 the three sequences compress from 596, 633 and 640 rows
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=3)
+    st = run_parity(wl, 640, prompts=[0, 37, 300], check_state_every_event=True)
+    lens = sorted({ev["len"] for orc in st["oracles"].values() for ev in orc.events})
+    _say(f"  lengths seen by compressions: {lens}")
+    assert {596, 633, 640} <= set(lens)
+
+
 @pytest.mark.parametrize("budget,steps", [(1024, 1408), (2048, 2432)])
 def test_cfg4_budgets(budget, steps):
     wl = CONFIGS["cfg4_b512"].with_(n_layers=1, batch=2, budget=budget)
@@ -184,20 +235,25 @@ def test_redundancy_cfg1_generic_fp32():
     wl = CONFIGS["cfg1_tiny"]
     st = run_parity(wl, 160, redundancy=dict(lam=0.7, tau=0.1, n_recent=wl.window))
     assert st["events"] == 6
-    _say(f"  ambiguous thresholds {st['ambiguous']} swaps {st['swaps']}")
+    _say(f"  entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) swaps {st['swaps']}")
+    assert st["ambiguous"] <= 2
 
 
 def test_redundancy_cfg3_shape_matrix_cores():
     wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
     st = run_parity(wl, 1024, redundancy=dict(lam=0.7, tau=0.5, n_recent=wl.window), check_state_every_event=False)
-    assert st["events"] == 4
-    _say(f"  ambiguous thresholds {st['ambiguous']} swaps {st['swaps']}")
+    assert st["events"] == 4 and st["pair_events"] == 16
+    _say(f"  entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) swaps {st['swaps']}")
+    # 64 head-events of ~4e5 cosines each, a 2e-6 wide band around tau: a handful, never a head's worth
+    assert st["ambiguous"] <= 400 and st["flipped"] <= st["ambiguous"]
 
 
 def test_redundancy_cfg5_shape_and_lambda_one():
     wl = CONFIGS["cfg5_large_batch"].with_(n_layers=1, batch=1)
     st = run_parity(wl, 1152, redundancy=dict(lam=0.9, tau=0.4, n_recent=0), check_state_every_event=False)
     assert st["events"] == 2
+    _say(f"  entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) swaps {st['swaps']}")
+    assert st["ambiguous"] <= 200
     # lambda = 1 must reproduce plain global-score eviction bit for bit
     wl2 = CONFIGS["cfg2_single_layer"]
     a = run_parity(wl2, 768, redundancy=dict(lam=1.0, tau=0.5, n_recent=0), check_state_every_event=False)
@@ -216,7 +272,7 @@ def test_redundancy_closed_form_duplicate_keys():
         K[..., n, n] = 2.0
     K[..., 9, :] = 0; K[..., 9, 3] = 5.0                    # row 9 duplicates the direction of row 3
     st.K.copy_(K.to(torch.bfloat16)); st.F.fill_(0.5)
-    _set_lengths(st, (l, l), step_next=l)
+    _set_lengths(st, (l, l), step_next=l, decoded=4)
     st.redundancy_combine(l - 1, lam=0.7, tau=0.5, n_recent=0, eps=0.0)
     R = st.R[0, 0, 0, :l].double().cpu().numpy()
     expect = np.full(l, np.exp(-1.0)); expect[[3, 9]] = 1.0
@@ -231,7 +287,7 @@ def test_pool_scores_against_oracle():
     c = l - w
     F = torch.rand(1, 2, 2, 64)
     st.F.copy_(F)
-    _set_lengths(st, (l, 20), step_next=l)                      # sequence 1 is below the budget: untouched
+    _set_lengths(st, (l, 20), step_next=l, decoded=w)           # sequence 1 is below the budget: untouched
     st.F_sel.fill_(-7.0)
     for kernel in (1, 5, 8, 200):
         st.ctx.pool_scores(st.F, st.d_state, l - 1, kernel, st.F_sel)
@@ -249,9 +305,11 @@ def _state(dtype="f32", **kw):
     return DecodeState(make_config(**base))
 
 
-def _set_lengths(st, lens, step_next, n_hist=(0, 0), n_tiled=(0, 0)):
-    """d_state for a 1-layer, 2-sequence state: lengths `lens` before decode step `step_next`."""
-    rec = [[lens[i], step_next, n_hist[i], n_tiled[i]] for i in range(2)]
+def _set_lengths(st, lens, step_next, n_hist=(0, 0), n_tiled=(0, 0), decoded=0):
+    """d_state for a 1-layer, 2-sequence state: lengths `lens` before decode step `step_next`, of
+    which the last `decoded` rows were decoded since the cache was loaded (compression wants a
+    full window of them, so tests of the compression calls pass decoded = w)."""
+    rec = [[lens[i] - decoded, step_next - decoded, n_hist[i], n_tiled[i]] for i in range(2)]
     st.d_state.copy_(torch.tensor([rec], dtype=torch.int32))
     st.len_host = max(lens)
 
@@ -350,7 +408,7 @@ def test_score_window_closed_form_equal_keys():
         l = st.cfg.budget + st.cfg.interval - 3
         st.K.fill_(0.5)
         st.qwin.copy_(torch.randn(st.qwin.shape).to(st.qwin.dtype))
-        _set_lengths(st, (l, l), step_next=l, n_tiled=(0, 32))     # constant keys: format does not matter
+        _set_lengths(st, (l, l), step_next=l, n_tiled=(0, 32), decoded=w)     # constant keys: format does not matter
         st.score_window(step=l - 1)
         c = l - w
         expect = sum(1.0 / (c + k + 1) for k in range(w)) / w
@@ -360,13 +418,30 @@ def test_score_window_closed_form_equal_keys():
 
 def test_eviction_is_a_noop_at_or_below_budget():
     st = _state()
-    _set_lengths(st, (32, 40), step_next=40)
+    _set_lengths(st, (32, 40), step_next=40, decoded=4)
     st.K.copy_(torch.randn(st.K.shape)); st.V.copy_(torch.randn(st.V.shape))
     st.qwin.copy_(torch.randn(st.qwin.shape))
     K0, V0 = st.K.clone(), st.V.clone()
     st.evict(step=39)
-    assert st.d_state.cpu().tolist() == [[[32, 40, 0, 0], [32, 40, 28, 32]]]
+    assert st.d_state.cpu().tolist() == [[[28, 36, 0, 0], [32, 40, 28, 32]]]
     assert torch.equal(st.K[0, 0], K0[0, 0]) and torch.equal(st.V[0, 0], V0[0, 0])     # sequence 0 untouched
+    assert not torch.equal(st.V[0, 1], V0[0, 1])
+
+
+def test_eviction_waits_for_a_full_window_of_generated_tokens():
+    # both sequences are above the budget (b = 32, w = 4) at the trigger, but sequence 0 has decoded
+    # only 3 tokens since its cache was loaded: its ring does not hold a window yet, nothing happens
+    st = _state()
+    st.d_state.copy_(torch.tensor([[[37, 37, 0, 0], [36, 36, 0, 0]]], dtype=torch.int32))
+    st.len_host = 40
+    st.K.copy_(torch.randn(st.K.shape)); st.V.copy_(torch.randn(st.V.shape))
+    st.qwin.copy_(torch.randn(st.qwin.shape))
+    K0, V0 = st.K.clone(), st.V.clone()
+    st.evicted.fill_(5)
+    st.score_window(39); st.global_update(39); st.select_topk(39); st.evicted_positions(39); st.compact(39)
+    assert st.d_state.cpu().tolist() == [[[37, 37, 0, 0], [32, 40, 28, 32]]]
+    assert torch.equal(st.K[0, 0], K0[0, 0]) and torch.equal(st.V[0, 0], V0[0, 0])
+    assert (st.evicted[0, 0] == -1).all() and (st.evicted[0, 1, :, :8] >= 0).all()
     assert not torch.equal(st.V[0, 1], V0[0, 1])
 
 
@@ -379,7 +454,7 @@ def test_global_update_three_forms_against_oracle():
         S = rng.random((1, 2, 2, 64)).astype(np.float32) ** 3
         H = rng.random((1, 2, 2, 64)).astype(np.float32)
         st.S.copy_(torch.from_numpy(S)); st.F_hist.copy_(torch.from_numpy(H))
-        _set_lengths(st, (l, l), step_next=l, n_hist=(0, 28))
+        _set_lengths(st, (l, l), step_next=l, n_hist=(0, 28), decoded=w)
         st.global_update(l - 1)
         F = st.F.cpu().numpy()
         for b, nh in enumerate((0, 28)):
@@ -391,7 +466,7 @@ def test_select_topk_ties_nan_and_brute_force():
     st = _state()
     l, w, k = 40, 4, 28
     c = l - w
-    _set_lengths(st, (l, l), step_next=l)
+    _set_lengths(st, (l, l), step_next=l, decoded=w)
     rng = np.random.default_rng(6)
     F = np.zeros((1, 2, 2, 64), np.float32)
     F[0, 0, 0, :c] = 0.25                                   # all tied: first k indices
@@ -419,7 +494,7 @@ def test_select_topk_random_shapes_signs_and_ties(seed):
     cap = (b + s_ + 31) // 32 * 32
     st = _state(budget=b, window=w, interval=s_, capacity=cap, n_q_heads=2, n_kv_heads=2)
     lens = (int(rng.integers(b + 1, b + s_ + 1)), b + s_)
-    _set_lengths(st, lens, step_next=1000)
+    _set_lengths(st, lens, step_next=1000, decoded=w)
     F = np.zeros((1, 2, 2, cap), np.float32)
     for bb in range(2):
         for j in range(2):
@@ -463,7 +538,7 @@ def test_compact_adversarial_keep_patterns(pattern, dtype, nt_old):
     # the first nt_old rows start in tiled format, the rest row-major (as appended)
     st.K.copy_(k_rows_to_cache(K, nt_old)); st.V.copy_(V); st.pos.copy_(pos); st.F.copy_(F)
     st.keep_idx.copy_(torch.from_numpy(keep_all))
-    _set_lengths(st, (l, l), step_next=500, n_tiled=(nt_old, nt_old))
+    _set_lengths(st, (l, l), step_next=500, n_tiled=(nt_old, nt_old), decoded=w)
     st.compact(step=499)
     assert st.d_state.cpu().tolist() == [[[b, 500, k, 160], [b, 500, k, 160]]]
     Kr = k_cache_to_rows(st.K, 160).cpu()

@@ -372,6 +372,65 @@ def test_trace_generator_is_chunking_invariant_and_dtype_exact():
     np.testing.assert_array_equal(bf16_round(k), k)
     qb, kb, vb = tr.batch_steps(50, 8)
     np.testing.assert_array_equal(qb[:, 0, 0], q[:8])
+    qn, kn, vn = tr.batch_steps(50, 8, need_q=False)             # prompts draw keys and values only
+    assert qn is None
+    np.testing.assert_array_equal(kn, kb); np.testing.assert_array_equal(vn, vb)
+
+
+# ------------------------------------------------------------------------ prompts ----
+def _steps_with_prompt(cfg, cls, P, t0, n_decode, **kw):
+    """Tokens t0-P .. t0-1 as a prompt, then n_decode decode steps from t0 (trace steps are positions)."""
+    tr = Trace(cfg)
+    q, k, v = tr.unit_steps(0, 0, 0, t0 + n_decode)
+    orc = cls(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.budget, cfg.window, cfg.interval, **kw)
+    orc.prefill(t0 - P, k[t0 - P:t0], v[t0 - P:t0])
+    outs = [orc.step(t, q[t], k[t], v[t]) for t in range(t0, t0 + n_decode)]
+    return orc, np.stack(outs)
+
+
+def test_prompt_within_budget_equals_decoding_it():
+    # A prompt of P <= b tokens leaves the state P decode steps leave (no compression can happen
+    # while the cache fits), so everything after it must agree with the run that decoded it.
+    cfg = SMALL
+    P = 7
+    ref, outs_ref, _ = _run(cfg, cfg.n_steps)
+    orc, outs = _steps_with_prompt(cfg, O.OracleA, P, P, cfg.n_steps - P, alpha=cfg.alpha)
+    np.testing.assert_array_equal(outs, outs_ref[P:])
+    np.testing.assert_array_equal(orc.pos, ref.pos)
+    np.testing.assert_array_equal(orc.F_hist, ref.F_hist)
+    assert len(orc.events) == len(ref.events) > 5
+
+
+@pytest.mark.parametrize("P,t0", [(5, 9), (12, 12), (0, 6)])
+def test_prompt_compacting_oracle_equals_mask_oracle(P, t0):
+    # shorter prompt than the common start (left-padded batch frame): positions t0-P .. t0-1
+    cfg = SMALL
+    a, outs_a = _steps_with_prompt(cfg, O.OracleA, P, t0, 50)
+    b, outs_b = _steps_with_prompt(cfg, O.OracleB, P, t0, 50)
+    assert len(a.events) == len(b.kept_log) > 5
+    np.testing.assert_allclose(outs_a, outs_b, rtol=1e-10, atol=1e-12)
+    for j in range(cfg.n_kv_heads):
+        assert a.pos[j, :a.len].tolist() == sorted(b.alive[j])
+
+
+def test_prompt_longer_than_budget_waits_for_a_full_window():
+    # b = 12, w = 3, s = 4.  Prompt of 20 rows, decoding from t0 = 22: the trigger after step 23 has
+    # seen only 2 generated tokens, fewer than the window, so nothing happens; the one after step 27
+    # compresses 26 rows down to the budget, window = the last 3 generated tokens.
+    cfg = SMALL
+    for cls in (O.OracleA, O.OracleB):
+        kw = dict(capacity=32) if cls is O.OracleA else {}
+        orc, _ = _steps_with_prompt(cfg, cls, 20, 22, 2, **kw)
+        n_ev = len(orc.events) if cls is O.OracleA else len(orc.kept_log)
+        assert n_ev == 0
+        orc, _ = _steps_with_prompt(cfg, cls, 20, 22, 6, **kw)
+        if cls is O.OracleA:
+            assert len(orc.events) == 1 and orc.events[0]["len"] == 26 and orc.len == cfg.budget
+            assert orc.pos[0, cfg.budget - 3:cfg.budget].tolist() == [25, 26, 27]
+            keep_a = [orc.pos[j, :orc.len].tolist() for j in range(cfg.n_kv_heads)]
+        else:
+            assert len(orc.kept_log) == 1
+            assert [sorted(x) for x in orc.alive] == keep_a
 
 
 # ------------------------------------------------------------- redundancy score ----
@@ -429,13 +488,27 @@ def test_redundancy_threshold_scale_invariance_and_hand_values():
             assert R[j, c] == pytest.approx(z[c] / sum(z), rel=1e-12)
 
 
-def test_redundancy_fp32_decisions_agree_away_from_the_threshold():
+def test_redundancy_parts_and_margin():
+    # the intermediates a checker may look at: C is the cosine matrix (symmetric, unit diagonal with
+    # eps = 0, equal to the hand values of the three-key example), col its thresholded column sums,
+    # the margin the distance of the nearest counted entry from tau
+    K = np.array([[[2.0, 0.0], [3.0, 4.0], [0.0, 5.0]]])
+    R, margin, parts = O.redundancy_score(K, 3, tau=0.5, eps=0.0, return_margin=True, return_parts=True)
+    np.testing.assert_allclose(parts["C"][0], [[1.0, 0.6, 0.0], [0.6, 1.0, 0.8], [0.0, 0.8, 1.0]], atol=1e-15)
+    np.testing.assert_allclose(parts["col"][0], [0.6, 1.4, 0.8], rtol=1e-15)
+    assert margin[0] == pytest.approx(0.1, rel=1e-12)                # |0.6 - 0.5|
+    np.testing.assert_allclose(R[0], sp_softmax(parts["col"][0]), rtol=1e-14)
+    # with the newest row exempt its column counts for nothing, and only entries of the other
+    # columns set the margin: |0.6 - 0.55| in column 0/1, not |0.8 - 0.55| ... of column 2
+    R, margin, parts = O.redundancy_score(K, 3, tau=0.55, n_recent=1, eps=0.0, return_margin=True, return_parts=True)
+    np.testing.assert_allclose(parts["col"][0], [0.6, 1.4, 0.0], rtol=1e-15)
+    assert margin[0] == pytest.approx(0.05, rel=1e-12)
     rng = np.random.default_rng(13)
-    K = rng.standard_normal((2, 40, 16)).astype(np.float32).astype(np.float64)
-    R64, m = O.redundancy_score(K, 40, 0.3, n_recent=4, return_margin=True)
-    R32 = O.redundancy_score(K, 40, 0.3, n_recent=4, fp32_decisions=True)
-    assert (m > 1e-5).all()                      # no entry near tau in this draw, so decisions agree
-    np.testing.assert_allclose(R32, R64, rtol=1e-5)
+    K = rng.standard_normal((2, 40, 16))
+    R, parts = O.redundancy_score(K, 40, 0.3, n_recent=4, return_parts=True)
+    C = parts["C"]
+    np.testing.assert_allclose(C, np.swapaxes(C, 1, 2), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(np.einsum("hii->hi", C), 1.0, rtol=1e-7)   # eps = 1e-8 in the norm
 
 
 def test_combine_redundancy_properties():
