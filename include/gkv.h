@@ -225,8 +225,9 @@ gkv_status gkv_pool_scores(gkv_ctx* ctx, const float* F, const int32_t* d_state,
  * generation are recorded and later build the sparse attention mask).  Call after
  * gkv_select_topk and BEFORE gkv_compact: writes, per unit, the original positions
  * (pos values) of the candidates that are not in keep_idx, ascending, padded with -1
- * to `interval` entries.  evicted [L,B,h_kv,interval].  Sequences not above the budget
- * get all -1.
+ * to capacity - b entries (a compression from l rows drops l - b of them: s in steady
+ * state, more when a prompt longer than the budget is compressed).
+ * evicted [L,B,h_kv,capacity-b].  Sequences that are not compressed get all -1.
  */
 gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const int32_t* pos,
                                  const int32_t* d_state, int32_t step, int32_t* evicted, void* stream);

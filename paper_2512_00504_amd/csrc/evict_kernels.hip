@@ -230,6 +230,8 @@ __global__ __launch_bounds__(256) void pool_scores_kernel(GkvDims dm, const floa
 }
 
 // ---- eviction log: original positions of the candidates that are about to be dropped -------
+// A compression from l rows drops l - b of them: s in steady state, up to capacity - b when a
+// prompt longer than the budget is compressed, hence capacity - b log entries per unit.
 // Dynamic LDS: uint32 kept[cap]
 __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, const int32_t* __restrict__ keep_idx,
                                                                 const int32_t* __restrict__ pos,
@@ -238,10 +240,11 @@ __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, cons
   extern __shared__ uint32_t kept[];
   __shared__ int tmp[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  int32_t* Eu = evicted + (size_t)unit * dm.s;
+  const int n_log = dm.cap - dm.b;
+  int32_t* Eu = evicted + (size_t)unit * n_log;
   const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
   if (l == 0) {
-    for (int i = tid; i < dm.s; i += 256) Eu[i] = -1;
+    for (int i = tid; i < n_log; i += 256) Eu[i] = -1;
     return;
   }
   const int c = l - dm.w, k = dm.b - dm.w;
@@ -260,10 +263,10 @@ __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, cons
   int out = block_inclusive_scan(n_out, tmp) - n_out;
   const int32_t* pu = pos + (size_t)unit * dm.cap;
   for (int n = lo; n < hi; ++n)
-    if (kept[n] == 0u && out < dm.s) Eu[out++] = pu[n];
-  // pad what is left (a full cache evicts exactly l - b <= s rows)
+    if (kept[n] == 0u && out < n_log) Eu[out++] = pu[n];
+  // pad what is left (exactly c - k = l - b rows are dropped when keep_idx holds k distinct candidates)
   const int total = c - k;
-  for (int i = total + tid; i < dm.s; i += 256) Eu[i] = -1;
+  for (int i = total + tid; i < n_log; i += 256) Eu[i] = -1;
 }
 
 __global__ void finalize_state_kernel(GkvDims dm, int32_t* d_state, int step) {

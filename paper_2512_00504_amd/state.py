@@ -63,7 +63,7 @@ class DecodeState:
         self.R = z(L, B, Hkv, cap, dtype=torch.float32)      # normalised redundancy score
         self.F_sel = z(L, B, Hkv, cap, dtype=torch.float32)  # lambda*F - (1-lambda)*R'
         self.keep_idx = z(L, B, Hkv, b - w, dtype=torch.int32)
-        self.evicted = torch.full((L, B, Hkv, cfg.interval), -1, dtype=torch.int32, device=dev)
+        self.evicted = torch.full((L, B, Hkv, cap - b), -1, dtype=torch.int32, device=dev)
         self.out = z(L, B, Hq, d, dtype=dt)
         self.workspace = torch.zeros(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
         self.ctx.workspace_init(self.workspace)

@@ -140,12 +140,13 @@ def upload_oracle_state(st: DecodeState, orc, l, b, next_step):
 
 
 def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_every_event=True,
-               cfg_over=None, fused_evict=False, redundancy=None, prompts=None, workers=8):
+               cfg_over=None, fused_evict=False, redundancy=None, prompts=None, workers=8, say=None):
     """Run GPU (all units) and oracle (the (layer, seq) `pairs`, default all) side by side for
     n_steps decode steps.  `prompts`: per-sequence prompt lengths P_i; the prompt of sequence i is
     the trace positions [t0 - P_i, t0) with t0 = max P_i, placed in the cache without decoding, and
     decoding starts at step t0 for every sequence.  Returns a dict of statistics.  Asserts parity at
-    every step (outputs) and every event (scores, kept sets, eviction log, cache contents)."""
+    every step (outputs) and every event (scores, kept sets, eviction log, cache contents).
+    `say`: optional print function, called once per chunk of steps (long runs show progress)."""
     tr = Trace(wl)
     st = DecodeState.from_workload(wl, params=params, **(cfg_over or {}))
     if pairs is None:
@@ -171,6 +172,8 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
             n = min(chunk, t0 - c0)
             _, k, v = tr.batch_steps(c0, n, workers=workers, need_q=False)
             st.load_prompt_rows(c0, torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev), t0, prompts)
+            if say:
+                say(f"    prompt rows {c0}..{c0 + n - 1} placed")
             for (l, b), orc in orcs.items():
                 lo = max(c0, t0 - prompts[b])
                 if lo < c0 + n:
@@ -243,6 +246,8 @@ def run_parity(wl, n_steps, pairs=None, params=None, chunk=128, check_state_ever
                     upload_oracle_state(st, orc, l, b, t + 1)
                 elif check_state_every_event:
                     check_state(st, orc, l, b, t + 1, f"state t={t} pair=({l},{b})")
+            if say and i == n - 1:
+                say(f"    steps {c0}..{t} checked, {stats['pair_events']} pair-events so far")
     for (l, b), orc in orcs.items():
         check_state(st, orc, l, b, t0 + n_steps, f"final state pair=({l},{b})")
     stats["state"] = st

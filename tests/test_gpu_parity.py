@@ -126,7 +126,7 @@ def test_cfg4_full_launch_sampled_pairs(name):
     wl = CONFIGS[name]
     _say(f"{name}: 28 layers x 16 sequences = {wl.n_units} units, prompt {wl.budget}, 2 cycles, 8 sampled pairs")
     st = run_parity(wl, 2 * wl.interval, pairs=CFG4_PAIRS, prompts=[wl.budget] * wl.batch,
-                    check_state_every_event=True, workers=16)
+                    check_state_every_event=True, workers=16, say=_say)
     assert st["events"] == 2 and st["pair_events"] == 16
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
@@ -135,7 +135,7 @@ def test_cfg5_full_launch_sampled_pairs():
     wl = CONFIGS["cfg5_large_batch"]
     _say(f"cfg5: 36 layers x 64 sequences = {wl.n_units} units, prompt {wl.budget}, 2 cycles, 8 sampled pairs")
     st = run_parity(wl, 2 * wl.interval, pairs=CFG5_PAIRS, prompts=[wl.budget] * wl.batch, chunk=64,
-                    check_state_every_event=True, workers=16)
+                    check_state_every_event=True, workers=16, say=_say)
     assert st["events"] == 2 and st["pair_events"] == 16
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
@@ -436,6 +436,7 @@ def test_eviction_waits_for_a_full_window_of_generated_tokens():
     st.len_host = 40
     st.K.copy_(torch.randn(st.K.shape)); st.V.copy_(torch.randn(st.V.shape))
     st.qwin.copy_(torch.randn(st.qwin.shape))
+    st.pos.copy_(torch.arange(64, dtype=torch.int32).expand(1, 2, 2, 64))
     K0, V0 = st.K.clone(), st.V.clone()
     st.evicted.fill_(5)
     st.score_window(39); st.global_update(39); st.select_topk(39); st.evicted_positions(39); st.compact(39)

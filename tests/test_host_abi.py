@@ -65,6 +65,31 @@ def test_create_validates_configuration():
     assert lib.gkv_status_string(6) == b"cache capacity exceeded"
 
 
+def test_create_rejects_shapes_whose_kernels_would_not_fit_lds():
+    # the plain attend kernel keeps 4 x float[capacity + 1 + d] in LDS: 66,576 bytes at capacity
+    # 4096, d = 64, over the 64 KiB a workgroup gets; 4000 rows fit
+    with pytest.raises(P.GkvError) as e:
+        P.Context(_cfg(budget=2048, interval=128, capacity=4096))
+    assert e.value.status == 2
+    P.Context(_cfg(budget=2048, interval=128, capacity=4000)).close()
+    with pytest.raises(P.GkvError) as e:       # bf16 too: "force_generic" may select the same kernel
+        P.Context(_cfg(budget=2048, interval=128, capacity=4096, dtype="bf16", head_dim=128, n_q_heads=14))
+    assert e.value.status == 2
+
+
+def test_split_count_raised_after_sizing_the_workspace_is_refused():
+    cfg = _cfg(dtype="bf16", head_dim=128, n_q_heads=14, budget=512, window=16, interval=128, capacity=640)
+    ctx = P.Context(cfg)
+    lib = P.load_library()
+    small = ctx.workspace_bytes()                       # sized without split-K partials
+    fake = ctypes.c_void_p(4096)                        # never dereferenced: the call fails before any launch
+    ctx.set_param("attend_splits", 3)
+    rc = lib.gkv_attend_decode(ctx.h, fake, fake, fake, fake, fake, fake, 0, fake, fake, 0, fake, fake, None)
+    assert rc == 3
+    assert ctx.workspace_bytes() > small                # sizing again covers the partials
+    ctx.close()
+
+
 def test_calls_reject_null_pointers_without_a_gpu():
     ctx = P.Context(_cfg())
     lib = P.load_library()
