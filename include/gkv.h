@@ -74,7 +74,8 @@ typedef enum {
   GKV_ERR_WORKSPACE = 3,     /* workspace pointer missing, or sized for fewer attend_splits */
   GKV_ERR_HIP = 4,           /* a HIP runtime call failed */
   GKV_ERR_UNSUPPORTED = 5,
-  GKV_ERR_OVERFLOW = 6       /* len_max_host would exceed the capacity */
+  GKV_ERR_OVERFLOW = 6,      /* len_max_host would exceed the capacity */
+  GKV_ERR_SCRATCH = 7        /* configuration too large for the fixed scratch array of gkv_evict_static */
 } gkv_status;
 
 typedef enum { GKV_F32 = 0, GKV_BF16 = 1 } gkv_dtype;
@@ -236,6 +237,25 @@ gkv_status gkv_evicted_positions(gkv_ctx* ctx, const int32_t* keep_idx, const in
 gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
                      int32_t* d_state, int32_t step, int32_t len_max_host,
                      float* S, float* F, int32_t* keep_idx, void* workspace, void* stream);
+
+/*
+ * gkv_evict for callers that cannot allocate device memory and have no buffers to spare for the
+ * intermediates: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same compression, same results in K, V, F_hist, pos and d_state; the local score,
+ * the global score and the kept indices live in a fixed array of GKV_STATIC_SCRATCH_BYTES bytes
+ * that is part of the library's device image (every GPU the library runs on holds it until the
+ * process ends).  The call allocates and frees nothing.  It needs
+ *   2 * align256(4 * L*B*h_kv * capacity) + align256(4 * L*B*h_kv * (b - w))
+ * bytes and returns GKV_ERR_SCRATCH, enqueuing nothing, if that exceeds the array (the 28-layer,
+ * batch-8, b = 512 shape needs 6.4 MB).  The device of `stream` must be the current device.
+ * Nothing in the array has to start at zero: every value read was written earlier in the same
+ * call.  All calls on one GPU share the array, whatever context or stream they use, so two calls
+ * that may overlap in time on one GPU race; serialise them (one stream, or events).
+ */
+#define GKV_STATIC_SCRATCH_BYTES (16u << 20)
+gkv_status gkv_evict_static(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,
+                            int32_t* d_state, int32_t step, int32_t len_max_host,
+                            void* workspace, void* stream);
 
 /*
  * Kernel timing for benchmarks.  While enabled, each kernel launch is bracketed

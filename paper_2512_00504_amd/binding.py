@@ -24,6 +24,7 @@ EXPORTS = [
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
     "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read", "gkv_redundancy_combine", "gkv_evicted_positions", "gkv_pool_scores",
+    "gkv_evict_static",
 ]
 
 
@@ -69,6 +70,7 @@ def load_library():
     lib.gkv_select_topk.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.gkv_evict_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.gkv_redundancy_combine.argtypes = [vp, vp, vp, i32, i32, vp, c_float, c_float, c_float, i32, vp, vp, vp, vp]
     lib.gkv_pool_scores.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.gkv_evicted_positions.argtypes = [vp, vp, vp, vp, i32, vp, vp]
@@ -170,6 +172,11 @@ class Context:
         self._check(self.lib.gkv_evict(self.h, _ptr(qwin), _ptr(K), _ptr(V), _ptr(F_hist), _ptr(pos),
                                        _ptr(d_state), step, len_max_host, _ptr(S), _ptr(F),
                                        _ptr(keep_idx), _ptr(workspace), _stream()), "gkv_evict")
+
+    def evict_static(self, qwin, K, V, F_hist, pos, d_state, step, len_max_host, workspace):
+        self._check(self.lib.gkv_evict_static(self.h, _ptr(qwin), _ptr(K), _ptr(V), _ptr(F_hist), _ptr(pos),
+                                              _ptr(d_state), step, len_max_host, _ptr(workspace), _stream()),
+                    "gkv_evict_static")
 
     def redundancy_combine(self, K, d_state, step, len_max_host, F, lam, tau, eps, n_recent, R_norm, F_sel, workspace):
         self._check(self.lib.gkv_redundancy_combine(self.h, _ptr(K), _ptr(d_state), step, len_max_host, _ptr(F),

@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -123,6 +124,7 @@ extern "C" const char* gkv_status_string(gkv_status st) {
     case GKV_ERR_HIP: return "HIP runtime error";
     case GKV_ERR_UNSUPPORTED: return "unsupported";
     case GKV_ERR_OVERFLOW: return "cache capacity exceeded";
+    case GKV_ERR_SCRATCH: return "configuration exceeds the static scratch array";
   }
   return "unknown status";
 }
@@ -309,6 +311,47 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
   st = gkv_select_topk(ctx, F, d_state, step, len_max_host, keep_idx, workspace, stream);
   if (st != GKV_OK) return st;
   return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace, stream);
+}
+
+// ---- compression for callers that cannot allocate ---------------------------------------------
+// The intermediates of one compression (S, F, keep_idx) live in a fixed array in device memory
+// that every GPU the library runs on holds until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; the address that kernels and copies use is the
+// one that call returns, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[GKV_STATIC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {};
+
+static gkv_status static_scratch_of_current_device(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return GKV_ERR_HIP;
+  if (dev < 0 || dev >= 64) return GKV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GKV_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return GKV_OK;
+}
+
+extern "C" gkv_status gkv_evict_static(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist,
+                                       int32_t* pos, int32_t* d_state, int32_t step, int32_t len_max_host,
+                                       void* workspace, void* stream) {
+  if (!ctx || !qwin || !K || !V || !F_hist || !pos || !d_state || step < 0) return GKV_ERR_INVALID_ARG;
+  const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
+  const size_t score_bytes = gkv_align256(units * ctx->dims.cap * sizeof(float));
+  const size_t keep_bytes = gkv_align256(units * (size_t)(ctx->dims.b - ctx->dims.w) * sizeof(int32_t));
+  if (2 * score_bytes + keep_bytes > (size_t)GKV_STATIC_SCRATCH_BYTES) return GKV_ERR_SCRATCH;
+  char* base = nullptr;
+  gkv_status st = static_scratch_of_current_device(&base);
+  if (st != GKV_OK) return st;
+  float* S = (float*)base;
+  float* F = (float*)(base + score_bytes);
+  int32_t* keep_idx = (int32_t*)(base + 2 * score_bytes);
+  return gkv_evict(ctx, qwin, K, V, F_hist, pos, d_state, step, len_max_host, S, F, keep_idx, workspace, stream);
 }
 
 extern "C" gkv_status gkv_redundancy_combine(gkv_ctx* ctx, const void* K, const int32_t* d_state, int32_t step,
