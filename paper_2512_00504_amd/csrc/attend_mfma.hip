@@ -94,7 +94,7 @@ struct Running {
 // the newest token from the inputs, mask the rest.  The common path has none of that.
 template <int KT, bool EDGE>
 __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const bf16x8 (&qB)[4], int it,
-                                              float scale_log2, int r, int kb, bool has_new, int len0,
+                                              float scale_log2, float scale_log2_lo, int r, int kb, bool has_new, int len0,
                                               int n_tot, const char* knew, const char* vnew) {
   // knew / vnew: the newest token's k and v rows, staged in LDS at the start of the workgroup
   constexpr int NS = 4 * KT;
@@ -136,7 +136,7 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
     sv[i] = sc[i >> 2][i & 3];
     if constexpr (EDGE) {
       const int key = key0 + (i >> 2) * 16 + 4 * kb + (i & 3);
-      if (key >= n_tot) sv[i] = -INFINITY;
+      if (key >= n_tot) sv[i] = -1e30f;              // finite: -inf times the (signed) low part of the scale would be NaN
     }
   }
   float mx = sv[0];
@@ -156,7 +156,9 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
   float psum = 0.f;
 #pragma unroll
   for (int i = 0; i < NS; ++i) {
-    pf[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], scale_log2, -st.m_run));
+    // exponent of 2 = z * (hi + lo) - m: the window-score kernel forms it identically, so the
+    // sums recorded below are the normalisers of its probabilities
+    pf[i] = __builtin_amdgcn_exp2f(fmaf(sv[i], scale_log2_lo, fmaf(sv[i], scale_log2, -st.m_run)));
     psum += pf[i];
   }
   st.l_run += psum;
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   const int len0 = length_before_step(seq, a.step, cap);
   const bool has_new = may_grow && (len0 < cap);
   const int n_tot = len0 + (has_new ? 1 : 0);
-  const float scale_log2 = dm.scale * 1.4426950408889634f;
+  const float scale_log2 = dm.scale_l2_hi, scale_log2_lo = dm.scale_l2_lo;
 
   Running st;
   st.m_run = -1e30f;
@@ -278,8 +280,8 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
   }
   __syncthreads();
   while (it < n_iter) {
-    if ((it + 1) * KEYS > len0) process_slice<KT, true>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
-    else process_slice<KT, false>(s, st, qB, it, scale_log2, r, kb, has_new, len0, n_tot, knew, vnew);
+    if ((it + 1) * KEYS > len0) process_slice<KT, true>(s, st, qB, it, scale_log2, scale_log2_lo, r, kb, has_new, len0, n_tot, knew, vnew);
+    else process_slice<KT, false>(s, st, qB, it, scale_log2, scale_log2_lo, r, kb, has_new, len0, n_tot, knew, vnew);
     it += stride;
     if (it < n_iter) issue_slice<KT>(s, Kh, Vh, it, seq.n_tiled, lane, r, kb);
   }
@@ -327,6 +329,10 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
       packed.x = (uint32_t)float_to_bf16_bits(o[0] * inv) | ((uint32_t)float_to_bf16_bits(o[1] * inv) << 16);
       packed.y = (uint32_t)float_to_bf16_bits(o[2] * inv) | ((uint32_t)float_to_bf16_bits(o[3] * inv) << 16);
       *(uint2*)(out + h * D + c4) = packed;
+      // softmax statistics of this head's row (running max in log2 units, sum), into the ring slot
+      // that also receives q: the window score of the next compression reuses them
+      if (c4 == 0 && a.write_stats)
+        a.ws.stats[((size_t)(a.step % dm.w) * dm.L * dm.B + lb) * dm.Hq + j * g + h] = make_float2(M, Lsum);
     } else {
       float* ph = part + h * PSTR;
       ph[c4] = o[0]; ph[c4 + 1] = o[1]; ph[c4 + 2] = o[2]; ph[c4 + 3] = o[3];

@@ -95,11 +95,21 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   d.b = cfg->budget; d.w = cfg->window; d.s = cfg->interval; d.cap = cfg->capacity;
   d.combine = cfg->combine; d.alpha = cfg->alpha;
   d.scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : (float)(1.0 / sqrt((double)cfg->head_dim));
+  {
+    const double sl2 = (double)d.scale * 1.4426950408889634074;
+    d.scale_l2_hi = (float)sl2;
+    d.scale_l2_lo = (float)(sl2 - (double)d.scale_l2_hi);
+  }
   c->esz = cfg->dtype == GKV_F32 ? 4 : 2;
   c->attend_splits = 0;
   c->ws_splits = 1;
   c->attend_tile = 16;
   c->force_generic = 0;
+  c->reuse_stats = 1;
+  c->stats_step = new (std::nothrow) int32_t[cfg->window];
+  if (!c->stats_step) { delete c; return GKV_ERR_INVALID_ARG; }
+  for (int i = 0; i < cfg->window; ++i) c->stats_step[i] = -1;
+  c->stats_ws = c->stats_K = c->stats_qwin = nullptr;
   c->mfma_ok = cfg->dtype == GKV_BF16 && d.d == 128 && d.g <= 16;
   c->prof = new (std::nothrow) GkvProfile();
   *out_ctx = c;
@@ -112,6 +122,7 @@ extern "C" void gkv_destroy(gkv_ctx* ctx) {
     for (int k = 0; k < GKV_K_COUNT; ++k) profile_drain(ctx->prof, k);
     delete ctx->prof;
   }
+  delete[] ctx->stats_step;
   delete ctx;
 }
 
@@ -146,6 +157,10 @@ int gkv_effective_splits(const gkv_ctx* ctx) {
   return s > m ? m : s;
 }
 
+static size_t ws_stats_bytes(const gkv_ctx* ctx) {
+  return (size_t)ctx->dims.w * ctx->dims.L * ctx->dims.B * ctx->dims.Hq * sizeof(float2);
+}
+
 // Split-K partials for `splits` workgroups per unit (none when a unit is not split).
 static size_t ws_partials_bytes(const gkv_ctx* ctx, int splits) {
   if (!ctx->mfma_ok || splits <= 1) return 0;
@@ -158,6 +173,7 @@ GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
   char* p = (char*)base;
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
   w.split_ticket = (int32_t*)p; p += gkv_align256(units * 4);
+  w.stats = (float2*)p; p += gkv_align256(ws_stats_bytes(ctx));
   w.partials = (float*)p;
   return w;
 }
@@ -167,7 +183,8 @@ extern "C" gkv_status gkv_workspace_bytes(gkv_ctx* ctx, size_t* out_bytes) {
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
   // the workspace is sized for the split count in force now; the decode call refuses a larger one
   ctx->ws_splits = gkv_effective_splits(ctx);
-  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_partials_bytes(ctx, ctx->ws_splits)) + 256;
+  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_stats_bytes(ctx)) +
+               gkv_align256(ws_partials_bytes(ctx, ctx->ws_splits)) + 256;
   return GKV_OK;
 }
 
@@ -214,6 +231,7 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     return GKV_OK;
   }
   if (!strcmp(name, "force_generic")) { ctx->force_generic = value != 0; return GKV_OK; }
+  if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
 }
 
@@ -229,6 +247,27 @@ static gkv_status check_len(const gkv_ctx* ctx, int32_t len_max_host, bool appen
 }
 static inline gkv_status hip_status(hipError_t e) { return e == hipSuccess ? GKV_OK : GKV_ERR_HIP; }
 
+// Host bookkeeping of the statistics ring: which decode step each slot's statistics belong to,
+// and for which buffers.  Everything is stream-ordered, so "enqueued" is as good as "written".
+static void note_stats(gkv_ctx* ctx, int32_t step, bool written, const void* ws, const void* K, const void* qwin) {
+  const int w = ctx->dims.w;
+  if (ws != ctx->stats_ws || K != ctx->stats_K || qwin != ctx->stats_qwin) {
+    for (int i = 0; i < w; ++i) ctx->stats_step[i] = -1;
+    ctx->stats_ws = ws; ctx->stats_K = K; ctx->stats_qwin = qwin;
+  }
+  ctx->stats_step[step % w] = written ? step : -1;
+}
+static bool stats_cover_window(const gkv_ctx* ctx, int32_t step, const void* ws, const void* K, const void* qwin) {
+  const int w = ctx->dims.w;
+  if (!ctx->reuse_stats || !ws || ws != ctx->stats_ws || K != ctx->stats_K || qwin != ctx->stats_qwin) return false;
+  if (step + 1 < w) return false;
+  for (int k = 0; k < w; ++k) {
+    const int t = step - w + 1 + k;
+    if (ctx->stats_step[t % w] != t) return false;
+  }
+  return true;
+}
+
 extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, const void* v_new,
                                         void* K, void* V, int32_t* pos, int32_t step, void* qwin,
                                         const int32_t* d_state, int32_t len_max_host, void* out,
@@ -239,7 +278,7 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
   if (st != GKV_OK) return st;
   AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_state, out, gkv_carve_workspace(ctx, workspace), 1,
-               ctx->attend_tile, 1};
+               ctx->attend_tile, 1, 0};
   {
     const size_t slot_bytes = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hq * ctx->dims.d * ctx->esz;
     a.copy_q = (const char*)q != (const char*)qwin + (size_t)(step % ctx->dims.w) * slot_bytes;
@@ -248,21 +287,31 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   if (use_mfma_attend(ctx)) {
     a.splits = gkv_effective_splits(ctx);
     if (a.splits > ctx->ws_splits) return GKV_ERR_WORKSPACE;   // partials would not fit the workspace as sized
+    // An unsplit appending step leaves (max, sum) of every query head's softmax in the ring slot
+    // of this step; the window score can then skip its own pass over the keys for them.
+    a.write_stats = a.splits == 1 && k_new != nullptr;
+    note_stats(ctx, step, a.write_stats != 0, workspace, K, qwin);
     return hip_status(gkv_launch_attend_mfma(ln, ctx->dims, a));
   }
+  note_stats(ctx, step, false, workspace, K, qwin);
   return hip_status(gkv_launch_attend_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 
 extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state,
                                        int32_t step, int32_t len_max_host, float* S,
                                        void* workspace, void* stream) {
-  (void)workspace;
   if (!ctx || !qwin || !K || !d_state || !S || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  ScoreArgs a{qwin, K, d_state, step, S};
+  ScoreArgs a{qwin, K, d_state, step, S, nullptr};
   GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
-  if (use_mfma_score(ctx)) return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
+  if (use_mfma_score(ctx)) {
+    // Under the causal reading of Eq. 1 a window row's softmax runs over exactly the keys its
+    // query attended to when it was decoded: if the last w decode calls on these buffers were the
+    // window's steps, their recorded (max, sum) are the row statistics and one pass suffices.
+    if (stats_cover_window(ctx, step, workspace, K, qwin)) a.stats = gkv_carve_workspace(ctx, workspace).stats;
+    return hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
+  }
   return hip_status(gkv_launch_score_generic(ln, ctx->dims, ctx->cfg.dtype, a));
 }
 

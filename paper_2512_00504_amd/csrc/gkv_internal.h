@@ -13,6 +13,10 @@ struct GkvDims {
   int32_t combine;
   float alpha;
   float scale;   // softmax scale of Eq. 1
+  // scale * log2(e) as an unevaluated sum hi + lo: the matrix-core kernels form the exponent of
+  // 2 as fma(z, lo, fma(z, hi, -m)), two roundings of a small number and no systematic error
+  // from a rounded scale, and the decode and window-score kernels form it the same way
+  float scale_l2_hi, scale_l2_lo;
 };
 
 struct GkvProfile;   // event pools, defined in gkv_api.hip
@@ -25,15 +29,25 @@ struct gkv_ctx {
   int32_t ws_splits;      // split count the workspace was sized for by gkv_workspace_bytes (1 = no partials)
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
+  int32_t reuse_stats;    // window score may reuse the softmax statistics the decode kernel recorded
   bool mfma_ok;           // bf16, d == 128, g <= 16
   GkvProfile* prof;
+  // Host record of which ring slots hold softmax statistics written by the matrix-core decode
+  // kernel: stats_step[slot] = decode step whose statistics the slot holds (-1 = none), valid for
+  // exactly these buffers.
+  int32_t* stats_step;    // [w]
+  const void* stats_ws; const void* stats_K; const void* stats_qwin;
 };
 
 // Workspace layout (bytes from the base):
 //   [0, 4*units)                    split tickets (int32, self-resetting)
+//   [.., + 8*w*L*B*h_q)             softmax statistics ring: per (slot, layer, sequence, query head)
+//                                   the running max (log2 units) and the sum of the decode step
+//                                   whose q sits in that slot of the window ring
 //   [.., + 4*units*splits*g*(d+2))  split-K partials (float)
 struct GkvWorkspace {
   int32_t* split_ticket;
+  float2* stats;
   float* partials;
 };
 
@@ -57,12 +71,14 @@ struct AttendArgs {
   void* K; void* V; int32_t* pos; int32_t step; void* qwin; const int32_t* d_state; void* out;
   GkvWorkspace ws; int32_t splits; int32_t tile_keys;
   int32_t copy_q;   // 0 when q already is the ring slot of this step
+  int32_t write_stats;   // record (max, sum) of every query head's softmax in ws.stats
 };
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);
 
 struct ScoreArgs {
   const void* qwin; const void* K; const int32_t* d_state; int32_t step; float* S;
+  const float2* stats;   // softmax statistics of the window's decode steps, or null: compute them
 };
 hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a);
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a);

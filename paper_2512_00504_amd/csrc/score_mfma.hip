@@ -5,10 +5,13 @@
 // staged in LDS once, in window-row order.  A wavefront takes 16-key tiles of K (one 1 KiB
 // contiguous load per 32 channels, thanks to the tiled K layout) and for every (head, block
 // of 16 window rows) computes logits^T[key, row] with 4 MFMA 16x16x32.
-//   pass 1: exact row statistics (max, sum of exp) of Eq. 1 over the keys each row saw;
-//   pass 2: logits again, p = exp(z - max)/sum, running max over the heads in registers
-//           (group max-reduce), then the sum over the 16 lanes that hold the window rows
-//           (Eq. 2).  Only S leaves the chip; the [g, w, l] matrix never exists in memory.
+//   row statistics (max, sum of exponentials) of Eq. 1 over the keys each window row saw: under
+//           the causal reading these are what the decode kernel computed when the row's query was
+//           decoded, and it records them next to the window ring; they are taken from there, or,
+//           when the last w decode calls were not this window's, computed by a first pass over K;
+//   scores: logits of the candidates, p = 2^(z*scale*log2e - max)/sum, running max over the
+//           heads in registers (group max-reduce), then the sum over the 16 lanes that hold the
+//           window rows (Eq. 2).  Only S leaves the chip; the [g, w, l] matrix never exists in memory.
 #include "gkv_internal.h"
 
 #ifndef GKV_SCORE_NW
@@ -29,23 +32,16 @@ constexpr int QSTR = ROW_BYTES + 16;       // padded LDS row of a staged query (
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *(const u32x4*)p; }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// e^x for x <= 0 to about 1.5 ulp in ~6 instructions: x*log2(e) is formed as an unevaluated
-// sum hi + lo (lo carries the rounding of the product and the low bits of log2 e), the hardware
-// exp2 takes hi, and 2^lo is applied as 1 + lo*ln2.  The plain library expf costs ~20.
-__device__ __forceinline__ float exp_fast(float x) {
-  x = fmaxf(x, -200.f);                                     // e^-200 is 0 in fp32; keeps -inf out of the fma
-  const float L2E_HI = 1.44269502162933349609375f;          // float(log2 e)
-  const float L2E_LO = 1.925963033500837e-8f;               // log2 e - L2E_HI
-  const float hi = x * L2E_HI;
-  const float lo = fmaf(x, L2E_HI, -hi) + x * L2E_LO;
-  const float e = __builtin_amdgcn_exp2f(hi);
-  return fmaf(e, lo * 0.693147180559945f, e);
-}
-
-// e^x for x <= 0 in 3 instructions, for sums: the argument's rounding costs up to |x| * 1e-7
-// relative, which only terms far below the maximum see, and those do not move a sum.
-__device__ __forceinline__ float exp_sum_term(float x) {
-  return __builtin_amdgcn_exp2f(fmaxf(x, -200.f) * 1.44269502162933349609375f);
+// Probabilities are 2^(z*(hi+lo) - m) / sum with hi + lo = scale * log2(e) as an unevaluated sum
+// and the exponent formed as fma(z, lo, fma(z, hi, -m)): the result of each fma is a small
+// number (the distance from the row maximum in log2 units), so its rounding costs ~1e-7
+// relative in the probability, and the rounding of the scale itself, which would act like a
+// slightly different softmax temperature, is carried by lo.  The hardware exp2 is good to 1 ulp.
+// The decode kernel forms its exponents the same way from bit-identical logits (same matrix-core
+// instruction sequence over the same operands), which is what makes its recorded (max, sum) the
+// row statistics of this kernel.
+__device__ __forceinline__ float exp2_of(float z, float m, float hi, float lo) {
+  return __builtin_amdgcn_exp2f(fmaf(z, lo, fmaf(z, hi, -m)));
 }
 
 // A operand of tile T: lane (row r, kblock kb) gets chunk 4c+kb of key 16T+r for c = 0..3; tiled
@@ -59,8 +55,10 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
   for (int c = 0; c < 4; ++c) kA[c] = ld16(p + c * step_off);
 }
 
-// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float redM[NW*G*w]; float redS[NW*G*w]
-template <int NW, int G, int WT>
+// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; and, when the row statistics
+// are computed here, float redM[NW*G*w]; float redS[NW*G*w]
+// HAVE_STATS: a.stats holds (max, sum) of every window row, recorded by the decode kernel.
+template <int NW, int G, int WT, bool HAVE_STATS>
 __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -78,8 +76,6 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   char* qs = smem_raw;
   float* rowM = (float*)(qs + ROWS * QSTR);
   float* rowZ = rowM + ROWS;
-  float* redM = rowZ + ROWS;
-  float* redS = redM + NW * ROWS;
 
   // stage the window queries: LDS row h*W + k holds head h, window row k (k-th oldest)
   for (int x = tid; x < ROWS * 16; x += NW * 64) {
@@ -90,84 +86,98 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     *(u32x4*)(qs + row * QSTR + ch * 16) =
         ld16((const char*)a.qwin + (((size_t)slot * dm.L * dm.B + lb) * dm.Hq + j * G + h) * (size_t)ROW_BYTES + ch * 16);
   }
+  if constexpr (HAVE_STATS) {
+    for (int x = tid; x < ROWS; x += NW * 64) {
+      const int h = x / W, k = x % W;
+      const int t_row = a.step - W + 1 + k;
+      const int slot = ((t_row % W) + W) % W;
+      const float2 ms = a.stats[((size_t)slot * dm.L * dm.B + lb) * dm.Hq + j * G + h];
+      rowM[x] = ms.x;
+      rowZ[x] = 1.f / ms.y;
+    }
+  }
   __syncthreads();
 
   const char* Kh = (const char*)a.K + (size_t)unit * cap * ROW_BYTES;
-  const float scale = dm.scale;
-  const int n_tiles = (l + 15) >> 4;
-
-  // ---- pass 1: row max and row sum over the keys visible to each window row -----------------
-  // Only the last tiles (those reaching into the window) need the causal mask; the running sum
-  // is rescaled only when some lane's maximum moved.
+  const float s_hi = dm.scale_l2_hi, s_lo = dm.scale_l2_lo;
   float rm[G][WT], rs[G][WT];
-#pragma unroll
-  for (int h = 0; h < G; ++h)
-#pragma unroll
-    for (int nt = 0; nt < WT; ++nt) { rm[h][nt] = -1e30f; rs[h][nt] = 0.f; }
 
-  for (int T = wave; T < n_tiles; T += NW) {
-    u32x4 kA[4];
-    load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
-    const int key_base = 16 * T + 4 * kb;
-    const bool full = 16 * T + 15 <= cc;                    // every row sees all 16 keys of this tile
+  if constexpr (!HAVE_STATS) {
+    // ---- pass 1: row max and row sum over the keys visible to each window row -----------------
+    // Only the last tiles (those reaching into the window) need the causal mask; the running sum
+    // is rescaled only when some lane's maximum moved.
+    float* redM = rowZ + ROWS;
+    float* redS = redM + NW * ROWS;
+    const int n_tiles = (l + 15) >> 4;
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int nt = 0; nt < WT; ++nt) { rm[h][nt] = -1e30f; rs[h][nt] = 0.f; }
+
+    for (int T = wave; T < n_tiles; T += NW) {
+      u32x4 kA[4];
+      load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
+      const int key_base = 16 * T + 4 * kb;
+      const bool full = 16 * T + 15 <= cc;                    // every row sees all 16 keys of this tile
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int nt = 0; nt < WT; ++nt) {
+          const char* qrow = qs + (h * W + 16 * nt + r) * QSTR;
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[c]),
+                                                          as_bf16x8(*(const u32x4*)(qrow + (4 * c + kb) * 16)),
+                                                          acc, 0, 0, 0);
+          float z[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) z[e] = acc[e];
+          if (!full) {
+            const int last_vis = cc + 16 * nt + r;            // row k sees keys [0, cc + k]
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (key_base + e > last_vis) z[e] = -1e30f;
+          }
+          const float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])) * s_hi;
+          if (__any(tm > rm[h][nt])) {
+            const float mnew = fmaxf(rm[h][nt], tm);
+            rs[h][nt] *= __builtin_amdgcn_exp2f(rm[h][nt] - mnew);
+            rm[h][nt] = mnew;
+          }
+          rs[h][nt] += (exp2_of(z[0], rm[h][nt], s_hi, s_lo) + exp2_of(z[1], rm[h][nt], s_hi, s_lo)) +
+                       (exp2_of(z[2], rm[h][nt], s_hi, s_lo) + exp2_of(z[3], rm[h][nt], s_hi, s_lo));
+        }
+    }
+    // merge the 4 lanes of a row, then the wavefronts
 #pragma unroll
     for (int h = 0; h < G; ++h)
 #pragma unroll
       for (int nt = 0; nt < WT; ++nt) {
-        const char* qrow = qs + (h * W + 16 * nt + r) * QSTR;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kA[c]),
-                                                        as_bf16x8(*(const u32x4*)(qrow + (4 * c + kb) * 16)),
-                                                        acc, 0, 0, 0);
-        float z[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) z[e] = acc[e] * scale;
-        if (!full) {
-          const int last_vis = cc + 16 * nt + r;            // row k sees keys [0, cc + k]
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (key_base + e > last_vis) z[e] = -INFINITY;
+        float m = rm[h][nt];
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));
+        float s = rs[h][nt] * __builtin_amdgcn_exp2f(rm[h][nt] - m);
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (kb == 0) {
+          redM[wave * ROWS + h * W + 16 * nt + r] = m;
+          redS[wave * ROWS + h * W + 16 * nt + r] = s;
         }
-        const float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-        if (__any(tm > rm[h][nt])) {
-          const float mnew = fmaxf(rm[h][nt], tm);
-          rs[h][nt] *= exp_fast(rm[h][nt] - mnew);
-          rm[h][nt] = mnew;
-        }
-        rs[h][nt] += (exp_sum_term(z[0] - rm[h][nt]) + exp_sum_term(z[1] - rm[h][nt])) +
-                     (exp_sum_term(z[2] - rm[h][nt]) + exp_sum_term(z[3] - rm[h][nt]));
       }
-  }
-  // merge the 4 lanes of a row, then the wavefronts
+    __syncthreads();
+    for (int x = tid; x < ROWS; x += NW * 64) {
+      float M = redM[x];
 #pragma unroll
-  for (int h = 0; h < G; ++h)
+      for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, redM[wv * ROWS + x]);
+      float Z = 0.f;
 #pragma unroll
-    for (int nt = 0; nt < WT; ++nt) {
-      float m = rm[h][nt];
-      m = fmaxf(m, __shfl_xor(m, 16));
-      m = fmaxf(m, __shfl_xor(m, 32));
-      float s = rs[h][nt] * exp_fast(rm[h][nt] - m);
-      s += __shfl_xor(s, 16);
-      s += __shfl_xor(s, 32);
-      if (kb == 0) {
-        redM[wave * ROWS + h * W + 16 * nt + r] = m;
-        redS[wave * ROWS + h * W + 16 * nt + r] = s;
-      }
+      for (int wv = 0; wv < NW; ++wv) Z += redS[wv * ROWS + x] * __builtin_amdgcn_exp2f(redM[wv * ROWS + x] - M);
+      rowM[x] = M;
+      rowZ[x] = 1.f / Z;                                       // one division per row, not per logit
     }
-  __syncthreads();
-  for (int x = tid; x < ROWS; x += NW * 64) {
-    float M = redM[x];
-#pragma unroll
-    for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, redM[wv * ROWS + x]);
-    float Z = 0.f;
-#pragma unroll
-    for (int wv = 0; wv < NW; ++wv) Z += redS[wv * ROWS + x] * exp_fast(redM[wv * ROWS + x] - M);
-    rowM[x] = M;
-    rowZ[x] = 1.f / Z;                                       // one division per row, not per logit
+    __syncthreads();
   }
-  __syncthreads();
 #pragma unroll
   for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
       rs[h][nt] = rowZ[h * W + 16 * nt + r];
     }
 
-  // ---- pass 2: probabilities, max over heads, mean over window rows -------------------------
+  // ---- probabilities of the candidates, max over heads, mean over window rows ---------------
   float* So = a.S + (size_t)unit * cap;
   const int cand_tiles = (cc + 15) >> 4;
   const float wf = (float)W;
@@ -199,7 +209,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           // candidates are visible to every window row; keys >= cc are discarded below
-          const float p = exp_fast(fminf(acc[e] * scale - rm[h][nt], 0.f)) * rs[h][nt];
+          const float p = exp2_of(acc[e], rm[h][nt], s_hi, s_lo) * rs[h][nt];
           amax[e] = fmaxf(amax[e], p);
         }
       }
@@ -222,9 +232,13 @@ template <int G, int WT>
 hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
   constexpr int NW = GKV_SCORE_NW;
   constexpr int ROWS = G * 16 * WT;
-  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
   const int units = dm.L * dm.B * dm.Hkv;
-  return gkv_launch(ln, score_mfma_kernel<NW, G, WT>, dim3(units), dim3(NW * 64), shmem, dm, a);
+  if (a.stats) {
+    const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * 2 * ROWS;
+    return gkv_launch(ln, score_mfma_kernel<NW, G, WT, true>, dim3(units), dim3(NW * 64), shmem, dm, a);
+  }
+  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
+  return gkv_launch(ln, score_mfma_kernel<NW, G, WT, false>, dim3(units), dim3(NW * 64), shmem, dm, a);
 }
 
 }  // namespace

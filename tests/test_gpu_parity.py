@@ -91,6 +91,38 @@ def test_cfg3_shape_32_key_slices():
     assert st["events"] == 2
 
 
+def test_cfg3_shape_window_score_computes_its_own_row_statistics():
+    # by default the window score takes the rows' softmax statistics from the decode kernel's
+    # record; with that switched off it computes them in a first pass over the keys
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
+    st = run_parity(wl, 768, params={"score_reuse_stats": 0}, check_state_every_event=False)
+    assert st["events"] == 2
+
+
+def test_window_score_with_and_without_recorded_statistics_agree():
+    # same state, both routes: each within 1e-5 of the oracle (checked in the whole-path tests),
+    # and within 3e-6 of each other
+    from gkv_traces import Trace
+    for name, over in (("cfg3_28layer_b512", dict(n_layers=2, batch=2)), ("cfg5_large_batch", dict(n_layers=1, batch=2))):
+        wl = CONFIGS[name].with_(**over)
+        tr = Trace(wl)
+        n = wl.budget + wl.interval
+        st = DecodeState.from_workload(wl)
+        q, k, v = [torch.from_numpy(x).to(torch.bfloat16).cuda() for x in tr.batch_steps(0, n)]
+        for t in range(n):
+            st.attend_decode(q[t], k[t], v[t], t)
+        assert st.is_trigger(n - 1)
+        st.score_window(n - 1)
+        S1 = st.S.clone()
+        st.ctx.set_param("score_reuse_stats", 0)
+        st.S.zero_()
+        st.score_window(n - 1)
+        c = n - wl.window
+        a, b = S1[..., :c].double().cpu().numpy(), st.S[..., :c].double().cpu().numpy()
+        assert (a > 0).any()
+        np.testing.assert_allclose(a, b, rtol=3e-6, atol=1e-30)
+
+
 def test_cfg3_full_size_sampled_units():
     # the launch configuration the benchmark times: all 896 units on the GPU, the oracle on a
     # sample of (layer, sequence) pairs that covers first/last layer and sequence
