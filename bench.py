@@ -137,6 +137,8 @@ def main():
                          "t %% w), so the decode kernel copies nothing; by default q is copied into the context's ring")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
+    ap.add_argument("--param", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a library tuning knob (gkv_set_param), e.g. compact_ppt=8; may be repeated")
     ap.add_argument("--fast-prefix", action="store_true",
                     help="fill the cache prefix by repeating the first s generated steps (for the largest workloads)")
     ap.add_argument("--no-full-launch", action="store_true",
@@ -189,6 +191,9 @@ def main():
         params["attend_splits"] = args.splits
     if args.tile:
         params["attend_tile"] = args.tile
+    for item in args.param:
+        name, val = item.split("=")
+        params[name] = int(val)
     # The layers are split into NS groups, each with its own context, buffers and HIP stream.
     # Every decode step launches every group; units are independent, so the groups' kernels may
     # overlap and one group's kernel boundary (launch, first-load latency, final stores) is
@@ -391,7 +396,7 @@ def main():
                    "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "budget": b, "window": wl.window, "interval": s, "alpha": wl.alpha,
                    "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
-                   "attend_splits": args.splits, "attend_tile": args.tile, "fast_prefix": args.fast_prefix,
+                   "attend_splits": args.splits, "attend_tile": args.tile, "params": params, "fast_prefix": args.fast_prefix,
                    "streams": NS, "layers_per_launch": Lg,
                    "redundancy": args.redundancy, "ring": "in place" if args.ring_in_place else "copy"},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",

@@ -127,7 +127,11 @@ int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_
 /* Tuning knobs (host only): "attend_splits" (workgroups per unit in the matrix-core
  * attend kernel; 0 = default = 1; set it before gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
  * the matrix-core attend kernel), "force_generic" (1 = use the plain vector-ALU
- * kernels even where matrix-core kernels exist). */
+ * kernels even where matrix-core kernels exist), "compact_ppt" (4, 8 or 16: 16-byte pieces
+ * a thread of the compaction kernel keeps in flight per round), "score_reuse_stats" (0 = the
+ * window score always computes its rows' softmax statistics itself instead of reusing the
+ * ones the matrix-core decode kernel recorded during the window's decode steps; see
+ * gkv_score_window). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*
@@ -159,6 +163,13 @@ gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void* k_new, con
  * (its ring slot), normalised over rows [0, c + k] (the keys it saw when decoded);
  * S[n] = (1/w) sum_k max_{heads of the group} A[head, k, n] for the candidates
  * n < c.  Entries n >= c are not written.  S [L,B,h_kv,capacity].
+ * Under this reading a window row's softmax runs over exactly the keys its query attended to
+ * when it was decoded.  The matrix-core decode kernel therefore records every query head's
+ * (max, sum) in the workspace, and when the last w gkv_attend_decode calls on this context
+ * with these same K, qwin and workspace pointers were the steps step-w+1 .. step (each
+ * appending a row), this call takes the rows' statistics from there and reads K once instead
+ * of twice.  Otherwise it computes them itself.  The caller must not change K rows or ring
+ * slots between those decode calls and this one (or sets "score_reuse_stats" to 0).
  */
 gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const void* K, const int32_t* d_state,
                             int32_t step, int32_t len_max_host, float* S,

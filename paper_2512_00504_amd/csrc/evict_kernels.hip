@@ -4,6 +4,9 @@
 
 namespace {
 
+// 16-byte piece as a native vector (arrays of it stay in registers; the runtime's uint4 class does not)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // ---- helpers -------------------------------------------------------------------------------
 // Inclusive scan over the 256 threads of a block; `tmp` holds 4 ints of LDS.
 __device__ __forceinline__ int block_inclusive_scan(int v, int* tmp) {
@@ -132,11 +135,13 @@ __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const floa
 // source piece of a chunk is loaded, then a barrier, then the stores.  Destination index <=
 // source index and sources ascend, so a chunk's stores (which stay inside the chunk's tiles)
 // never touch a row that a later chunk still has to read.
+// Dynamic LDS: int keep_s[b - w]: the kept indices, read from memory once.
 template <int PPT>
 __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const int32_t* __restrict__ keep_idx,
                                                       const float* __restrict__ F, void* K, void* V,
                                                       float* __restrict__ F_hist, int32_t* pos,
                                                       const int32_t* __restrict__ d_state, int step) {
+  extern __shared__ int keep_s[];
   __shared__ int red_i[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const bool isK = blockIdx.y == 0;
@@ -149,8 +154,11 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
 
   // first destination row whose source differs from it; a K format change rewrites everything
   int first = k;
-  for (int n = tid; n < k; n += 256)
-    if (Ku[n] != n) { first = n; break; }        // ascending per thread: the first hit is its minimum
+  for (int n = tid; n < k; n += 256) {
+    const int src = Ku[n];
+    keep_s[n] = src;
+    if (src != n && first == k) first = n;       // ascending per thread: the first hit is its minimum
+  }
   for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o));
   if ((tid & 63) == 0) red_i[tid >> 6] = first;
   __syncthreads();
@@ -162,7 +170,7 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
     float* Hu = F_hist + (size_t)unit * dm.cap;
     const float* Fu = F + (size_t)unit * dm.cap;
     for (int n = tid; n < k; n += 256) {
-      int src = Ku[n];
+      int src = keep_s[n];
       src = src < 0 ? 0 : (src >= c ? c - 1 : src);
       Hu[n] = Fu[src];
     }
@@ -171,34 +179,36 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
   const int NP = dm.d * esz / 16;                // 16-byte pieces per row
   int R = (256 * PPT) / NP;                      // rows per chunk: whole tiles, at most one per thread
   R = (R > 256 ? 256 : R) & ~15;
-  uint4* base = (uint4*)((char*)(isK ? K : V) + (size_t)unit * dm.cap * dm.d * esz);
+  u32x4* base = (u32x4*)((char*)(isK ? K : V) + (size_t)unit * dm.cap * dm.d * esz);
   int32_t* pu = pos + (size_t)unit * dm.cap;
 
+  // Every load of a round is issued before the first wait: the addresses are computed without
+  // branches (pieces beyond the chunk or the budget read row 0, always in bounds, and are not
+  // stored), so the PPT 16-byte loads of a thread are in flight together.
   for (int r0 = first; r0 < b; r0 += R) {
-    uint4 buf[PPT];
+    u32x4 buf[PPT];
     int dst[PPT];
-    int pos_val = 0;
 #pragma unroll
     for (int i = 0; i < PPT; ++i) {
       const int x = tid + 256 * i;
       const int rr = x / NP, piece = x % NP;
       const int row = r0 + rr;
-      dst[i] = -1;
-      if (rr < R && row < b) {
-        int src = row < k ? Ku[row] : c + (row - k);
-        src = src < 0 ? 0 : (src >= l ? l - 1 : src);
-        const int so = (isK && src < nt_old) ? ((src >> 4) * 16 * NP + piece * 16 + (src & 15)) : (src * NP + piece);
-        dst[i] = (isK && row < nt_new) ? ((row >> 4) * 16 * NP + piece * 16 + (row & 15)) : (row * NP + piece);
-        buf[i] = base[so];
-      }
+      const bool valid = rr < R && row < b;
+      int src = keep_s[row < k ? row : 0];
+      src = row < k ? src : c + (row - k);
+      src = src < 0 ? 0 : (src >= l ? l - 1 : src);
+      src = valid ? src : 0;
+      const int so = (isK && src < nt_old) ? ((src >> 4) * 16 * NP + piece * 16 + (src & 15)) : (src * NP + piece);
+      const int d_o = (isK && row < nt_new) ? ((row >> 4) * 16 * NP + piece * 16 + (row & 15)) : (row * NP + piece);
+      dst[i] = valid ? d_o : -1;
+      buf[i] = base[so];
     }
     const int prow = r0 + tid;
     const bool do_pos = isK && tid < R && prow < b;
-    if (do_pos) {
-      int src = prow < k ? Ku[prow] : c + (prow - k);
-      src = src < 0 ? 0 : (src >= l ? l - 1 : src);
-      pos_val = pu[src];
-    }
+    int psrc = keep_s[prow < k ? prow : 0];
+    psrc = prow < k ? psrc : c + (prow - k);
+    psrc = psrc < 0 ? 0 : (psrc >= l ? l - 1 : psrc);
+    const int pos_val = pu[do_pos ? psrc : 0];
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < PPT; ++i)
@@ -301,7 +311,10 @@ hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, c
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
                               int32_t* d_state, int32_t step) {
   const int units = dm.L * dm.B * dm.Hkv;
-  hipError_t e = gkv_launch(ln, compact_kernel<4>, dim3(units, 2), dim3(256), 0, dm, esz, keep_idx, F, K, V,
+  const size_t shmem = sizeof(int) * (size_t)(dm.b - dm.w);
+  const int ppt = ln.ctx ? ln.ctx->compact_ppt : 8;
+  auto kern = ppt == 16 ? compact_kernel<16> : ppt == 8 ? compact_kernel<8> : compact_kernel<4>;
+  hipError_t e = gkv_launch(ln, kern, dim3(units, 2), dim3(256), shmem, dm, esz, keep_idx, F, K, V,
                             F_hist, pos, (const int32_t*)d_state, (int)step);
   if (e != hipSuccess) return e;
   const int nlb = dm.L * dm.B;

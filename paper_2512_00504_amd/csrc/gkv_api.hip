@@ -106,6 +106,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   c->attend_tile = 16;
   c->force_generic = 0;
   c->reuse_stats = 1;
+  c->compact_ppt = 8;
   c->stats_step = new (std::nothrow) int32_t[cfg->window];
   if (!c->stats_step) { delete c; return GKV_ERR_INVALID_ARG; }
   for (int i = 0; i < cfg->window; ++i) c->stats_step[i] = -1;
@@ -231,6 +232,11 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     return GKV_OK;
   }
   if (!strcmp(name, "force_generic")) { ctx->force_generic = value != 0; return GKV_OK; }
+  if (!strcmp(name, "compact_ppt")) {
+    if (value != 4 && value != 8 && value != 16) return GKV_ERR_INVALID_ARG;
+    ctx->compact_ppt = value;
+    return GKV_OK;
+  }
   if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
 }

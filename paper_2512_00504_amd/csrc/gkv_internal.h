@@ -29,6 +29,7 @@ struct gkv_ctx {
   int32_t ws_splits;      // split count the workspace was sized for by gkv_workspace_bytes (1 = no partials)
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
+  int32_t compact_ppt;    // 16-byte pieces per thread and chunk round of the compaction kernel: 4, 8 or 16
   int32_t reuse_stats;    // window score may reuse the softmax statistics the decode kernel recorded
   bool mfma_ok;           // bf16, d == 128, g <= 16
   GkvProfile* prof;
