@@ -1,21 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the G-KV decode/evict hot path on one MI355X.
 
-A "step" is one decode step of the whole path for the whole batch: one
-gkv_attend_decode launch covering every layer, plus, every s steps, one
-compression (gkv_score_window, gkv_global_update, gkv_select_topk,
-gkv_compact).  The timed region is K consecutive steady-state steps (cache
-length cycling b+1 .. b+s) on synthetic inputs that are already resident in
-HBM; it is bracketed by device synchronisation on both sides.
+A "step" is one decode step of the whole path for the whole batch: gkv_attend_decode over every
+layer, plus, every s steps, one compression (gkv_score_window, gkv_global_update,
+gkv_select_topk, gkv_compact).  The timed region is whole steady-state compression cycles
+(cache length cycling b+1 .. b+s), at least TEN of them whatever --steps says, on synthetic
+inputs that are already resident in HBM; it is bracketed by device synchronisation on both
+sides (wall clock, the figure `value` is computed from) and by HIP events on the launch streams.
 
-Prints ONE JSON line: metric/value (tokens/s = batch * K / seconds), the
-roofline object of the dominant kernel (attend) from per-launch HIP events
-recorded on the launch stream, and the CPU oracle's rate on a bounded sample.
+Prints ONE JSON line: metric/value (tokens/s = batch * steps / seconds); `roofline`, the attend
+kernel against the HBM peak from per-launch HIP events on the launch stream; the same for a
+second workload whose K+V cache is more than twice the 256 MB memory-side cache
+(`roofline_out_of_cache`); the rate a no-arithmetic reader with the kernel's access pattern gets on
+the same caches (`read_ceiling`); and the CPU oracle's rate on a bounded sample (`cpu_baseline`).
 """
 import argparse
 import ctypes
 import json
 import os
+import statistics
 import subprocess
 import sys
 import time
@@ -25,6 +28,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+MIN_TIMED_CYCLES = 10
+CPU_WORKERS_MAX = 16             # the CPU share of a one-GPU machine, whatever its nproc says
+OUT_OF_CACHE_WORKLOAD = "cfg4_b512"   # 587 MB of K+V: more than twice the memory-side cache
 
 
 # ------------------------------------------------------------------------------------------------
@@ -62,7 +68,8 @@ def cpu_worker(workload: str, layer: int, seq: int, seconds: float, combine: str
 def cpu_baseline(workload: str, seconds: float, combine: str, alpha: float):
     from gkv_traces import CONFIGS
     wl = CONFIGS[workload]
-    n_workers = max(1, min(16, os.cpu_count() or 1, wl.n_layers * wl.batch))
+    nproc = os.cpu_count() or 1
+    n_workers = max(1, min(CPU_WORKERS_MAX, nproc, wl.n_layers * wl.batch))
     procs = []
     for i in range(n_workers):
         layer, seq = (i * 7) % wl.n_layers, i % wl.batch
@@ -78,10 +85,12 @@ def cpu_baseline(workload: str, seconds: float, combine: str, alpha: float):
         total_steps += rec["pair_steps"]
     # a decoded token needs one step of every layer of its sequence
     tokens_per_s = rate / wl.n_layers
-    return {"value": tokens_per_s, "unit": "tokens/s", "cores": n_workers, "kind": "oracle",
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": n_workers, "nproc": nproc, "kind": "oracle",
             "sample": (f"{n_workers} (layer, sequence) pairs of {wl.n_layers * wl.batch}, steady-state "
                        f"cycles of {wl.interval} steps + 1 compression, {total_steps} pair-steps in "
-                       f"~{seconds:.0f} s per worker, one thread each; scaled by 1/n_layers")}
+                       f"~{seconds:.0f} s per worker, one single-threaded process per pair (the box reports "
+                       f"nproc = {nproc}; at most {CPU_WORKERS_MAX} are used, the CPU share of one GPU); "
+                       f"scaled by 1/n_layers")}
 
 
 # ------------------------------------------------------------------------------------------------
@@ -100,108 +109,42 @@ def algorithmic_bytes(wl):
         "global": units * 4 * ((b - w) + (l - w)),
         "topk": units * (4 * (l - w) + 4 * (b - w)),
         "compact": units * 2 * (2 * e * d + 8) * b,
+        "redundancy": units * (e * d * l + 12 * l),
     }
 
 
-def read_traffic(workload: str):
-    """HBM bytes per attend launch from the committed rocprofv3 --pmc summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"attend_{workload}_pmc.txt")
+def read_traffic(workload: str, tag: str):
+    """HBM bytes per attend launch from the committed rocprofv3 --pmc summary of this workload, if any
+    (counters cannot be read from inside the run; the file names the command that produced it)."""
+    name = f"attend_{workload}_{tag}_pmc.txt"
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, "profiles", name)) as f:
             for line in f:
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return float(line.split(":")[1])
+                    return float(line.split(":")[1]), "profiles/" + name
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1280)
-    ap.add_argument("--warmup", type=int, default=256)
-    ap.add_argument("--workload", default="cfg3_28layer_b512")
-    ap.add_argument("--combine", choices=["max", "avg", "sum"], default=None,
-                    help="global-score form (default: the workload's, max)")
-    ap.add_argument("--alpha", type=float, default=None, help="memory-decay rate (default: the workload's, 0.8)")
-    ap.add_argument("--redundancy", nargs=2, type=float, metavar=("LAMBDA", "TAU"), default=None,
-                    help="select on lambda*F - (1-lambda)*R' (redundancy score with threshold TAU, the window "
-                         "rows exempt): the paper's full G-KV; the CPU baseline leg is then skipped")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="split the layers into this many groups, each launched on its own HIP stream")
-    ap.add_argument("--ring-in-place", action="store_true",
-                    help="treat the pre-uploaded q tensors as the window ring itself (q of step t already is slot "
-                         "t %% w), so the decode kernel copies nothing; by default q is copied into the context's ring")
-    ap.add_argument("--splits", type=int, default=0)
-    ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
-    ap.add_argument("--param", action="append", default=[], metavar="NAME=VALUE",
-                    help="set a library tuning knob (gkv_set_param), e.g. compact_ppt=8; may be repeated")
-    ap.add_argument("--fast-prefix", action="store_true",
-                    help="fill the cache prefix by repeating the first s generated steps (for the largest workloads)")
-    ap.add_argument("--no-full-launch", action="store_true",
-                    help="skip the extra pass that times the attend kernel launched once for all layers")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="run only a plain 1 GiB device copy (for scaling rocprofv3 --pmc counters)")
-    ap.add_argument("--cpu-worker", nargs=6, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS", "COMBINE", "ALPHA"))
-    args = ap.parse_args()
-
-    if args.cpu_worker:
-        wlname, layer, seq, secs, comb, alpha = args.cpu_worker
-        cpu_worker(wlname, int(layer), int(seq), float(secs), comb, float(alpha))
-        return
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
-        sys.exit(2)
-
-    from gkv_traces import CONFIGS, Trace
-    wl = CONFIGS[args.workload]
-    if args.combine is not None:
-        wl = wl.with_(combine=args.combine)
-    if args.alpha is not None:
-        wl = wl.with_(alpha=args.alpha)
-
-    # CPU leg first, before this process touches the GPU (children are plain CPU processes)
-    cpu = None
-    if not args.no_cpu_baseline and not args.copy_calibration and args.redundancy is None:
-        cpu = cpu_baseline(args.workload, args.cpu_seconds, wl.combine, wl.alpha)
-
+def run_workload(wl, args, n_streams, timed_cycles, warm_cycles, kernel_cycles, full_launch, params, workers):
+    """Set up `wl` on the GPU in steady state, time `timed_cycles` compression cycles, then measure
+    per-launch kernel durations and the read ceiling on the same caches.  Returns a dict."""
     import torch
+    from gkv_traces import Trace
+    from paper_2512_00504_amd.binding import probe_attend_read
     from paper_2512_00504_amd.state import DecodeState
     dev = torch.device("cuda:0")
-
-    if args.copy_calibration:
-        n = 1 << 30
-        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
-        return
-
-    s, b = wl.interval, wl.budget
-    K = max(s, (args.steps + s - 1) // s * s)            # whole compression cycles
-    W = max(s, (args.warmup + s - 1) // s * s)
-    preroll = b                                          # tokens placed in the cache before step b
-    params = {}
-    if args.splits:
-        params["attend_splits"] = args.splits
-    if args.tile:
-        params["attend_tile"] = args.tile
-    for item in args.param:
-        name, val = item.split("=")
-        params[name] = int(val)
+    s, b, w = wl.interval, wl.budget, wl.window
+    assert b % s == 0 and s % w == 0
+    mfma = wl.dtype == "bf16" and wl.head_dim == 128
     # The layers are split into NS groups, each with its own context, buffers and HIP stream.
     # Every decode step launches every group; units are independent, so the groups' kernels may
     # overlap and one group's kernel boundary (launch, first-load latency, final stores) is
     # covered by the other group's streaming.  NS = 1 is the plain one-launch-per-step form.
-    NS = max(1, min(args.streams, wl.n_layers))
-    bounds = [wl.n_layers * g // NS for g in range(NS + 1)]          # as even as possible
+    NS = max(1, min(n_streams, wl.n_layers))
+    bounds = [wl.n_layers * g // NS for g in range(NS + 1)]
     Lgs = [bounds[g + 1] - bounds[g] for g in range(NS)]
-    Lg = max(Lgs)
     tr = Trace(wl)
     dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     esz = 2 if wl.dtype == "bf16" else 4
@@ -215,22 +158,20 @@ def main():
             for st in groups]
     host = {"len": 0}
     rings = [None] * NS
-    assert s % wl.window == 0
 
     def split_layers(x):
         """[n, L, ...] numpy -> per-group contiguous device tensors [n, layers of the group, ...]."""
         return [torch.from_numpy(x[:, bounds[g]:bounds[g + 1]]).to(dt).to(dev).contiguous() for g in range(NS)]
 
     def upload(t0, n):
-        q, k, v = tr.batch_steps(t0, n, workers=8)
+        q, k, v = tr.batch_steps(t0, n, workers=workers)
         return list(zip(split_layers(q), split_layers(k), split_layers(v)))
 
-    def run(chunk, t0, n, stream_of):
+    def run(chunk, t0, n, stream_of, cycle_events=None):
         """n decode steps starting at absolute step t0 on pre-uploaded inputs; raw C calls."""
         len_host = host["len"]
         addr = [(qd.data_ptr(), qd.stride(0) * esz, kd.data_ptr(), kd.stride(0) * esz, vd.data_ptr(), vd.stride(0) * esz)
                 for (qd, kd, vd) in chunk]
-        w = wl.window
         for i in range(n):
             t = t0 + i
             for g in range(NS):
@@ -267,6 +208,13 @@ def main():
                         raise RuntimeError(f"compression failed: {rc}")
                 len_host = b
         host["len"] = len_host
+        if cycle_events is not None:
+            evs = []
+            for g in range(NS):
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record(streams[g])
+                evs.append(ev)
+            cycle_events.append(evs)
 
     own_streams = [ctypes.c_void_p(st_.cuda_stream) for st_ in streams]
     one_stream = [own_streams[0]] * NS
@@ -275,12 +223,12 @@ def main():
     # cache exceeds the budget, so this is the state b decode steps leave behind, and every
     # attend launch of this process then runs at a steady-state length b+1 .. b+s.
     if args.fast_prefix:
-        _, k0, v0 = tr.batch_steps(0, s, workers=8)
+        _, k0, v0 = tr.batch_steps(0, s, workers=workers, need_q=False)
         reps = (b + s - 1) // s
         k0s = [x.repeat(reps, 1, 1, 1, 1)[:b] for x in split_layers(k0)]
         v0s = [x.repeat(reps, 1, 1, 1, 1)[:b] for x in split_layers(v0)]
     else:
-        _, k0, v0 = tr.batch_steps(0, b, workers=8)
+        _, k0, v0 = tr.batch_steps(0, b, workers=workers, need_q=False)
         k0s, v0s = split_layers(k0), split_layers(v0)
     for g, st in enumerate(groups):
         st.load_prefix(k0s[g], v0s[g])
@@ -288,8 +236,7 @@ def main():
     host["len"] = b
     torch.cuda.synchronize()
     t_abs = b
-    assert b % s == 0 and W >= s, "warm-up must cover one whole compression cycle"
-    for c0 in range(0, W, s):                             # untimed warm-up cycles (first compression)
+    for _ in range(max(1, warm_cycles)):                  # untimed warm-up cycles (first compression)
         chunk = upload(t_abs, s)
         torch.cuda.synchronize()
         run(chunk, t_abs, s, own_streams)
@@ -299,24 +246,31 @@ def main():
         lens = st.lengths(t_abs)
         assert int(lens.max()) == b and int(lens.min()) == b
 
-    chunks = [upload(t_abs + c0, s) for c0 in range(0, K, s)]     # all timed inputs resident in HBM
+    # ---- the timed region: whole compression cycles, inputs resident in HBM ---------------------
+    K = timed_cycles * s
+    chunks = [upload(t_abs + c * s, s) for c in range(timed_cycles)]
     torch.cuda.synchronize()
+    cyc = []
+    run([], 0, 0, own_streams, cyc)                       # records the start events, enqueues nothing else
     t_wall = time.perf_counter()
     for ci, chunk in enumerate(chunks):
-        run(chunk, t_abs + ci * s, s, own_streams)
+        run(chunk, t_abs + ci * s, s, own_streams, cyc)
     torch.cuda.synchronize()
-    elapsed = wall_s = time.perf_counter() - t_wall
-    gpu_s = None
+    wall_s = time.perf_counter() - t_wall
+    start = cyc[0]
+    gpu_s = 1e-3 * max(start[h].elapsed_time(cyc[-1][g]) for g in range(NS) for h in range(NS))
+    cyc_ms = [max(cyc[c][g].elapsed_time(cyc[c + 1][g]) for g in range(NS)) for c in range(timed_cycles)]
     t_abs += K
 
-    # per-kernel durations: the same steps again with every launch bracketed by its own HIP events,
-    # all groups on ONE stream so that a launch's duration is the kernel's own (no overlap)
+    # ---- per-kernel durations: a few of the same cycles again with every launch bracketed by its
+    # own HIP events, all groups on ONE stream so that a launch's duration is the kernel's own
     for st in groups:
         st.ctx.profile_reset()
         st.ctx.profile_enable(True)
-    for ci, chunk in enumerate(chunks):
+    for ci, chunk in enumerate(chunks[:kernel_cycles]):
         run(chunk, t_abs + ci * s, s, one_stream)
     torch.cuda.synchronize()
+    t_abs += kernel_cycles * s
     per_kernel = {}
     for name in ("attend", "score", "global", "topk", "compact") + (("redundancy",) if args.redundancy else ()):
         ms = n = 0
@@ -325,13 +279,65 @@ def main():
             m_, n_ = st.ctx.profile_read(name)
             ms += m_; n += n_
         per_kernel[name] = {"launches": n, "avg_us": (1e3 * ms / n) if n else None}
-    st = groups[0]
 
-    # The same kernel launched once for all layers (one context, one stream): its duration at the
-    # full 28-layer shape, for comparison with the per-group launches above.  The cache contents
-    # are the groups' current ones, the inputs the timed chunks.
-    full = None
-    if NS > 1 and not args.no_full_launch:
+    alg = algorithmic_bytes(wl)                       # whole batch, all layers
+    for name in per_kernel:
+        us = per_kernel[name]["avg_us"]
+        per_kernel[name]["algorithmic_MB"] = alg[name] / NS / 1e6
+        per_kernel[name]["GBps"] = (alg[name] / NS / (us * 1e-6) / 1e9) if us else None
+        per_kernel[name]["hbm_frac"] = (per_kernel[name]["GBps"] / HBM_PEAK_GBS) if us else None
+
+    # ---- the read ceiling on these very caches: the decode kernel's access pattern, no arithmetic
+    def ceiling(K_t, V_t):
+        if not mfma:
+            return None
+        rows = (b + s // 2) // 16 * 16
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            probe_attend_read(K_t, V_t, rows, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 40
+        e0.record()
+        for _ in range(reps):
+            probe_attend_read(K_t, V_t, rows, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        units = K_t.numel() // (K_t.shape[-2] * K_t.shape[-1])
+        nbytes = units * rows * 512
+        us = 1e3 * e0.elapsed_time(e1) / reps
+        return {"units": units, "rows": rows, "bytes_per_launch": nbytes, "avg_launch_us": us,
+                "GBps": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+    ceil_group = ceiling(groups[0].K, groups[0].V)
+
+    # the same reader on every group's cache at once, each on its group's stream, as the timed
+    # region runs the decode kernel: the ceiling for the overlapped launches
+    ceil_overlap = None
+    if mfma and NS > 1:
+        rows = (b + s // 2) // 16 * 16
+        sinks = [torch.zeros(4, dtype=torch.int32, device=dev) for _ in range(NS)]
+        reps = 40
+        torch.cuda.synchronize()
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in range(NS)]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in range(NS)]
+        for g in range(NS):
+            e0[g].record(streams[g])
+        for _ in range(reps):
+            for g in range(NS):
+                with torch.cuda.stream(streams[g]):
+                    probe_attend_read(groups[g].K, groups[g].V, rows, sinks[g])
+        for g in range(NS):
+            e1[g].record(streams[g])
+        torch.cuda.synchronize()
+        ms = max(e0[h].elapsed_time(e1[g]) for g in range(NS) for h in range(NS))
+        nbytes = sum(st.K.numel() // (st.K.shape[-2] * st.K.shape[-1]) for st in groups) * rows * 512
+        ceil_overlap = {"bytes_per_round": nbytes, "avg_round_us": 1e3 * ms / reps,
+                        "GBps": nbytes * reps / (ms * 1e-3) / 1e9, "hbm_frac": nbytes * reps / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    # ---- the same kernel launched once for all layers (one context, one stream): its duration at
+    # the full shape.  The cache contents are the groups' current ones, the inputs the timed chunks.
+    full = ceil_full = None
+    if NS > 1 and full_launch:
         fs = DecodeState.from_workload(wl, device=dev, params=params)
         for name in ("K", "V", "pos", "F_hist"):
             getattr(fs, name).copy_(torch.cat([getattr(g_, name) for g_ in groups], dim=0))
@@ -339,8 +345,8 @@ def main():
         fs.d_state.copy_(torch.cat([g_.d_state for g_ in groups], dim=0))
         fs.len_host = host["len"]
         fs.ctx.profile_enable(True)
-        t_f = t_abs + K
-        for ci, chunk in enumerate(chunks[:4]):
+        t_f = t_abs
+        for ci, chunk in enumerate(chunks[:kernel_cycles]):
             qf, kf, vf = [torch.cat([chunk[g][i] for g in range(NS)], dim=1).contiguous() for i in range(3)]
             for i in range(s):
                 fs.attend_decode(qf[i], kf[i], vf[i], t_f)
@@ -351,69 +357,185 @@ def main():
         ms, n = fs.ctx.profile_read("attend")
         fs.ctx.profile_enable(False)
         us = 1e3 * ms / n
-        full = {"launches": n, "avg_launch_us": us, "algorithmic_bytes_per_launch": algorithmic_bytes(wl)["attend"],
-                "achieved": algorithmic_bytes(wl)["attend"] / (us * 1e-6) / 1e9,
-                "frac": algorithmic_bytes(wl)["attend"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "unit": "GB/s"}
+        full = {"launches": n, "avg_launch_us": us, "algorithmic_bytes_per_launch": alg["attend"],
+                "achieved": alg["attend"] / (us * 1e-6) / 1e9,
+                "frac": alg["attend"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "unit": "GB/s"}
+        ceil_full = ceiling(fs.K, fs.V)
         del fs
 
-    # read bandwidth a trivial streaming kernel sustains on this GPU, for context: over a buffer
-    # far larger than any cache, and over one the size of this workload's K+V cache
-    from paper_2512_00504_amd.binding import probe_stream_read
-    sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    ceilings = {}
-    for label, nbytes in (("4GiB", 4 << 30), ("kv_cache_size", int(st.K.numel() * st.K.element_size() * 2 * NS))):
-        buf = torch.empty(nbytes // 16 * 16, dtype=torch.uint8, device=dev).fill_(3)
-        for _ in range(3):
-            probe_stream_read(buf, sink)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 10
-        e0.record()
-        for _ in range(reps):
-            probe_stream_read(buf, sink)
-        e1.record()
-        torch.cuda.synchronize()
-        ceilings[label] = {"bytes": buf.numel(), "GBps": buf.numel() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9}
-        del buf
-
-    alg = algorithmic_bytes(wl)                       # whole batch, all layers
     att_us = per_kernel["attend"]["avg_us"]           # one launch = one group = n_layers / NS layers
     achieved = alg["attend"] / NS / (att_us * 1e-6) / 1e9
-    alg["redundancy"] = wl.n_units * ((2 if wl.dtype == "bf16" else 4) * wl.head_dim * (b + s) + 12 * (b + s))
-    for name in per_kernel:
-        us = per_kernel[name]["avg_us"]
-        per_kernel[name]["algorithmic_MB"] = alg[name] / NS / 1e6
-        per_kernel[name]["GBps"] = (alg[name] / NS / (us * 1e-6) / 1e9) if us else None
-        per_kernel[name]["hbm_frac"] = (per_kernel[name]["GBps"] / HBM_PEAK_GBS) if us else None
-    bytes_per_step = alg["attend"] + (alg["score"] + alg["global"] + alg["topk"] + alg["compact"]) / s
-    tokens_per_s = wl.batch * K / elapsed
+    evict_bytes = alg["score"] + alg["global"] + alg["topk"] + alg["compact"] + (alg["redundancy"] if args.redundancy else 0)
+    bytes_per_step = alg["attend"] + evict_bytes / s
+    kv_bytes = sum(st.K.numel() * esz * 2 for st in groups)
+    tag = f"s{NS}"
+    traffic, traffic_src = read_traffic(wl.name, tag)
+    return {
+        "workload": wl.name, "steps": K, "cycles": timed_cycles, "streams": NS, "layers_per_launch": max(Lgs),
+        "tokens_per_s": wl.batch * K / wall_s, "ms_per_step": 1e3 * wall_s / K,
+        "wall_seconds": wall_s, "gpu_seconds": gpu_s,
+        "tokens_per_s_gpu_clock": wl.batch * K / gpu_s,
+        "cycle_ms": {"min": min(cyc_ms), "median": statistics.median(cyc_ms), "max": max(cyc_ms)},
+        "kv_cache_bytes": kv_bytes,
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if mfma else "attend_generic_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
+                     "algorithmic_bytes_per_launch": alg["attend"] / NS, "avg_launch_us": att_us,
+                     "launches_per_step": NS, "launches_timed": per_kernel["attend"]["launches"],
+                     "note": "launch durations from HIP events on the launch stream, the groups' launches "
+                             "serialised on one stream so that a duration is the kernel's own; the timed region "
+                             "runs the groups on separate streams"},
+        "roofline_all_layers_one_launch": full,
+        "read_ceiling": {"per_group_launch": ceil_group, "all_layers": ceil_full, "groups_overlapped": ceil_overlap,
+                         "note": "the decode kernel's load pattern with no arithmetic, merge or stores, on the same caches"},
+        "whole_step": {"algorithmic_bytes_per_step": bytes_per_step,
+                       "GBps": bytes_per_step * K / wall_s / 1e9,
+                       "hbm_frac": bytes_per_step * K / wall_s / 1e9 / HBM_PEAK_GBS,
+                       "cache_assisted": kv_bytes < 2 * (256 << 20),
+                       "note": ("K+V cache of %.0f MB against a 256 MB memory-side cache: part of every step's reads is "
+                                "served from that cache, so this is a rate in algorithmic bytes, not pure HBM traffic"
+                                % (kv_bytes / 1e6)) if kv_bytes < 2 * (256 << 20) else
+                               ("K+V cache of %.0f MB, more than twice the 256 MB memory-side cache" % (kv_bytes / 1e6))},
+        "per_kernel": per_kernel,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1280)
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--workload", default="cfg3_28layer_b512")
+    ap.add_argument("--combine", choices=["max", "avg", "sum"], default=None,
+                    help="global-score form (default: the workload's, max)")
+    ap.add_argument("--alpha", type=float, default=None, help="memory-decay rate (default: the workload's, 0.8)")
+    ap.add_argument("--redundancy", nargs=2, type=float, metavar=("LAMBDA", "TAU"), default=None,
+                    help="select on lambda*F - (1-lambda)*R' (redundancy score with threshold TAU, the window "
+                         "rows exempt): the paper's full G-KV; the CPU baseline leg is then skipped")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="split the layers into this many groups, each launched on its own HIP stream")
+    ap.add_argument("--ring-in-place", action="store_true",
+                    help="treat the pre-uploaded q tensors as the window ring itself (q of step t already is slot "
+                         "t %% w), so the decode kernel copies nothing; by default q is copied into the context's ring")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--tile", type=int, default=0, help="attend_tile knob (16 or 32); 0 = library default")
+    ap.add_argument("--param", action="append", default=[], metavar="NAME=VALUE",
+                    help="set a library tuning knob (gkv_set_param), e.g. compact_ppt=8; may be repeated")
+    ap.add_argument("--fast-prefix", action="store_true",
+                    help="fill the cache prefix by repeating the first s generated steps (for the largest workloads)")
+    ap.add_argument("--min-cycles", type=int, default=MIN_TIMED_CYCLES,
+                    help="time at least this many compression cycles whatever --steps says")
+    ap.add_argument("--no-full-launch", action="store_true",
+                    help="skip the extra pass that times the attend kernel launched once for all layers")
+    ap.add_argument("--no-out-of-cache-leg", action="store_true",
+                    help="skip the second workload (K+V cache over twice the memory-side cache) of the default run")
+    ap.add_argument("--leg", action="store_true",
+                    help="(internal) run as the second workload of a default run: print the workload's own record")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--cpu-worker", nargs=6, metavar=("WORKLOAD", "LAYER", "SEQ", "SECONDS", "COMBINE", "ALPHA"))
+    args = ap.parse_args()
+
+    if args.cpu_worker:
+        wlname, layer, seq, secs, comb, alpha = args.cpu_worker
+        cpu_worker(wlname, int(layer), int(seq), float(secs), comb, float(alpha))
+        return
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    from gkv_traces import CONFIGS
+    wl = CONFIGS[args.workload]
+    if args.combine is not None:
+        wl = wl.with_(combine=args.combine)
+    if args.alpha is not None:
+        wl = wl.with_(alpha=args.alpha)
+
+    # CPU leg first, before this process touches the GPU (children are plain CPU processes)
+    cpu = None
+    if not args.no_cpu_baseline and not args.copy_calibration and not args.leg and args.redundancy is None:
+        cpu = cpu_baseline(args.workload, args.cpu_seconds, wl.combine, wl.alpha)
+
+    # Second workload of the default run: the same shape at batch 16, whose 587 MB of K+V cannot sit
+    # in the 256 MB memory-side cache.  Same measurement, fewer cycles, in a process of its own that
+    # has finished before this one touches the GPU (a fresh address space and allocator state).
+    ooc = None
+    if (wl.name == "cfg3_28layer_b512" and not args.no_out_of_cache_leg and not args.leg
+            and not args.copy_calibration and args.redundancy is None):
+        cmd = [sys.executable, os.path.abspath(__file__), "--leg", "--workload", OUT_OF_CACHE_WORKLOAD,
+               "--min-cycles", "4", "--steps", "1", "--warmup", "1", "--streams", str(args.streams),
+               "--combine", wl.combine, "--alpha", str(wl.alpha)]
+        for item in args.param:
+            cmd += ["--param", item]
+        if args.ring_in_place:
+            cmd.append("--ring-in-place")
+        if args.no_full_launch:
+            cmd.append("--no-full-launch")
+        child = subprocess.run(cmd, stdout=subprocess.PIPE, text=True, cwd=ROOT)
+        if child.returncode != 0:
+            raise RuntimeError(f"out-of-cache leg failed with status {child.returncode}")
+        ooc = json.loads(child.stdout.strip().splitlines()[-1])
+
+    import torch
+    dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
+        return
+
+    s, b = wl.interval, wl.budget
+    timed_cycles = max(args.min_cycles, (args.steps + s - 1) // s, 1)     # whole compression cycles
+    warm_cycles = max(1, (args.warmup + s - 1) // s)
+    params = {}
+    if args.splits:
+        params["attend_splits"] = args.splits
+    if args.tile:
+        params["attend_tile"] = args.tile
+    for item in args.param:
+        name, val = item.split("=")
+        params[name] = int(val)
+    workers = max(1, min(CPU_WORKERS_MAX, os.cpu_count() or 1))
+
+    res = run_workload(wl, args, args.streams, timed_cycles, warm_cycles, kernel_cycles=min(2, timed_cycles),
+                       full_launch=not args.no_full_launch, params=params, workers=workers)
+
+    if args.leg:
+        print(json.dumps({k: res[k] for k in ("workload", "kv_cache_bytes", "steps", "streams", "tokens_per_s",
+                                              "ms_per_step", "roofline", "roofline_all_layers_one_launch",
+                                              "read_ceiling", "whole_step", "per_kernel")}))
+        return
+
     out = {
         "metric": "decode tokens/sec through attend+score+evict at budget 512; % HBM roofline"
                   if b == 512 else f"decode tokens/sec through attend+score+evict at budget {b}",
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak",
+        "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": res["steps"], "warmup": warm_cycles * s,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "n_layers": wl.n_layers, "batch": wl.batch,
                    "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
                    "budget": b, "window": wl.window, "interval": s, "alpha": wl.alpha,
-                   "combine": wl.combine, "trace": wl.recipe, "preroll_steps": preroll,
-                   "attend_splits": args.splits, "attend_tile": args.tile, "params": params, "fast_prefix": args.fast_prefix,
-                   "streams": NS, "layers_per_launch": Lg,
-                   "redundancy": args.redundancy, "ring": "in place" if args.ring_in_place else "copy"},
-        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attend_generic_kernel",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(wl.name),
-                     "algorithmic_bytes_per_launch": alg["attend"] / NS, "avg_launch_us": att_us,
-                     "launches_per_step": NS,
-                     "note": "launch durations from HIP events with the launches serialised on one stream; "
-                             "the timed region overlaps the groups' launches on separate streams"},
-        "roofline_all_layers_one_launch": full,
+                   "combine": wl.combine, "trace": wl.recipe, "preroll_steps": b,
+                   "params": params, "fast_prefix": args.fast_prefix,
+                   "streams": res["streams"], "layers_per_launch": res["layers_per_launch"],
+                   "redundancy": args.redundancy, "ring": "in place" if args.ring_in_place else "copy",
+                   "steps_requested": args.steps, "timed_cycles": res["cycles"],
+                   "note": f"the timed region is whole compression cycles, at least {args.min_cycles}"},
+        "roofline": res["roofline"],
+        "roofline_all_layers_one_launch": res["roofline_all_layers_one_launch"],
+        "roofline_out_of_cache": ooc,
+        "read_ceiling": res["read_ceiling"],
         "cpu_baseline": cpu,
-        "whole_step": {"algorithmic_bytes_per_step": bytes_per_step,
-                       "GBps": bytes_per_step * K / elapsed / 1e9,
-                       "hbm_frac": bytes_per_step * K / elapsed / 1e9 / HBM_PEAK_GBS,
-                       "gpu_seconds": gpu_s, "wall_seconds": wall_s},
-        "per_kernel": per_kernel,
-        "stream_read_ceiling": ceilings,
+        "whole_step": dict(res["whole_step"], wall_seconds=res["wall_seconds"], gpu_seconds=res["gpu_seconds"],
+                           tokens_per_s_gpu_clock=res["tokens_per_s_gpu_clock"], cycle_ms=res["cycle_ms"]),
+        "per_kernel": res["per_kernel"],
     }
     print(json.dumps(out))
 

@@ -268,27 +268,6 @@ gkv_status gkv_evict_static(gkv_ctx* ctx, const void* qwin, void* K, void* V, fl
                             int32_t* d_state, int32_t step, int32_t len_max_host,
                             void* workspace, void* stream);
 
-/*
- * Kernel timing for benchmarks.  While enabled, each kernel launch is bracketed
- * by HIP events on the launch stream that record the kernel's own begin and
- * end; gkv_profile_read synchronises those events and returns the total
- * milliseconds and launch count of one kernel class since the last reset.
- */
-typedef enum {
-  GKV_K_ATTEND = 0, GKV_K_SCORE = 1, GKV_K_GLOBAL = 2, GKV_K_TOPK = 3, GKV_K_COMPACT = 4,
-  GKV_K_REDUNDANCY = 5, GKV_K_COUNT = 6
-} gkv_kernel_id;
-gkv_status gkv_profile_enable(gkv_ctx* ctx, int32_t on);
-gkv_status gkv_profile_read(gkv_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches);
-gkv_status gkv_profile_reset(gkv_ctx* ctx);
-
-/*
- * Measurement aid, not part of the method: enqueues a plain streaming read of `bytes` bytes
- * of device memory at `src` (16-byte loads, 2048 workgroups); `sink` is 4 bytes of device
- * memory.  Timing it gives the read bandwidth the GPU sustains, a ceiling to compare with.
- */
-gkv_status gkv_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

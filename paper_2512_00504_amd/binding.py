@@ -23,7 +23,7 @@ EXPORTS = [
     "gkv_create", "gkv_destroy", "gkv_status_string", "gkv_workspace_bytes", "gkv_workspace_init",
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
-    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_stream_read", "gkv_redundancy_combine", "gkv_evicted_positions", "gkv_pool_scores",
+    "gkv_profile_read", "gkv_profile_reset", "gkv_probe_attend_read", "gkv_redundancy_combine", "gkv_evicted_positions", "gkv_pool_scores",
     "gkv_evict_static",
 ]
 
@@ -77,7 +77,7 @@ def load_library():
     lib.gkv_profile_enable.argtypes = [vp, i32]
     lib.gkv_profile_read.argtypes = [vp, i32, POINTER(c_double), POINTER(c_int64)]
     lib.gkv_profile_reset.argtypes = [vp]
-    lib.gkv_probe_stream_read.argtypes = [vp, c_size_t, vp, vp]
+    lib.gkv_probe_attend_read.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("gkv_destroy", "gkv_status_string", "gkv_k_offset"):
@@ -203,12 +203,15 @@ class Context:
         return ms.value, n.value
 
 
-def probe_stream_read(src, sink):
-    """Enqueue one streaming read of the whole tensor `src` (measurement aid)."""
+def probe_attend_read(K, V, rows, sink):
+    """Enqueue one pass of the decode kernel's read pattern over rows [0, rows) of every unit of the
+    bf16, d = 128 caches K, V [..., capacity, 128] (measurement aid)."""
     lib = load_library()
-    st = lib.gkv_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream())
+    cap = K.shape[-2]
+    units = K.numel() // (cap * K.shape[-1])
+    st = lib.gkv_probe_attend_read(_ptr(K), _ptr(V), units, cap, rows, _ptr(sink), _stream())
     if st != 0:
-        raise GkvError(st, "gkv_probe_stream_read")
+        raise GkvError(st, "gkv_probe_attend_read")
 
 
 def cache_bytes(cfg: GkvConfig, rows: int, score_elem_bytes: int = 4):

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "gkv.h"
+#include "gkv_bench.h"
 
 // Dimensions every kernel needs, passed by value.
 struct GkvDims {

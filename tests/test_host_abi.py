@@ -27,7 +27,8 @@ def _golden(name):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "gkv.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", name)).read()
+                     for name in sorted(os.listdir(os.path.join(ROOT, "include"))) if name.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(gkv_[a-z_0-9]+)\s*\(", header))
     assert {"gkv_attend_decode", "gkv_score_window", "gkv_global_update", "gkv_select_topk",
