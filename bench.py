@@ -250,17 +250,54 @@ def run_workload(wl, args, n_streams, timed_cycles, warm_cycles, kernel_cycles, 
     K = timed_cycles * s
     chunks = [upload(t_abs + c * s, s) for c in range(timed_cycles)]
     torch.cuda.synchronize()
-    cyc = []
-    run([], 0, 0, own_streams, cyc)                       # records the start events, enqueues nothing else
-    t_wall = time.perf_counter()
-    for ci, chunk in enumerate(chunks):
-        run(chunk, t_abs + ci * s, s, own_streams, cyc)
-    torch.cuda.synchronize()
-    wall_s = time.perf_counter() - t_wall
-    start = cyc[0]
-    gpu_s = 1e-3 * max(start[h].elapsed_time(cyc[-1][g]) for g in range(NS) for h in range(NS))
-    cyc_ms = [max(cyc[c][g].elapsed_time(cyc[c + 1][g]) for g in range(NS)) for c in range(timed_cycles)]
-    t_abs += K
+    if not args.graph:
+        cyc = []
+        run([], 0, 0, own_streams, cyc)                   # records the start events, enqueues nothing else
+        t_wall = time.perf_counter()
+        for ci, chunk in enumerate(chunks):
+            run(chunk, t_abs + ci * s, s, own_streams, cyc)
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t_wall
+        start = cyc[0]
+        gpu_s = 1e-3 * max(start[h].elapsed_time(cyc[-1][g]) for g in range(NS) for h in range(NS))
+        cyc_ms = [max(cyc[c][g].elapsed_time(cyc[c + 1][g]) for g in range(NS)) for c in range(timed_cycles)]
+        t_abs += K
+    else:
+        # The same launches recorded once into a HIP graph (one branch per layer group) and replayed
+        # with a single call: the step number comes from a device-side step base that the graph
+        # itself advances, so the recording is valid for every replay.  Replays reuse the inputs
+        # of the recorded cycles.
+        bases = [torch.tensor([t_abs], dtype=torch.int32, device=dev) for _ in range(NS)]
+        for g, st in enumerate(groups):
+            st.ctx.set_step_base(bases[g])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=streams[0]):
+            for g in range(1, NS):
+                streams[g].wait_stream(streams[0])
+            for ci, chunk in enumerate(chunks):
+                run(chunk, ci * s, s, own_streams)        # steps relative to the step base
+            for g in range(NS):
+                if lib.gkv_advance_step_base(ptrs[g]["h"], K, own_streams[g]):
+                    raise RuntimeError("gkv_advance_step_base failed")
+            for g in range(1, NS):
+                streams[0].wait_stream(streams[g])
+        torch.cuda.synchronize()
+        with torch.cuda.stream(streams[0]):
+            graph.replay()                                # untimed: first replay uploads the graph
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t_wall = time.perf_counter()
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            wall_s = time.perf_counter() - t_wall
+        gpu_s = 1e-3 * e0.elapsed_time(e1)
+        cyc_ms = [1e3 * gpu_s / timed_cycles]
+        t_abs += 2 * K
+        assert all(int(x.item()) == t_abs for x in bases)
+        for st in groups:
+            st.ctx.set_step_base(None)
 
     # ---- per-kernel durations: a few of the same cycles again with every launch bracketed by its
     # own HIP events, all groups on ONE stream so that a launch's duration is the kernel's own
@@ -431,6 +468,9 @@ def main():
                     help="skip the extra pass that times the attend kernel launched once for all layers")
     ap.add_argument("--no-out-of-cache-leg", action="store_true",
                     help="skip the second workload (K+V cache over twice the memory-side cache) of the default run")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the timed cycles into one HIP graph (one branch per layer group, device-side step "
+                         "base) and time a single replay instead of launching call by call")
     ap.add_argument("--leg", action="store_true",
                     help="(internal) run as the second workload of a default run: print the workload's own record")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -526,6 +566,7 @@ def main():
                    "params": params, "fast_prefix": args.fast_prefix,
                    "streams": res["streams"], "layers_per_launch": res["layers_per_launch"],
                    "redundancy": args.redundancy, "ring": "in place" if args.ring_in_place else "copy",
+                   "launch": "one HIP graph replay" if args.graph else "call by call",
                    "steps_requested": args.steps, "timed_cycles": res["cycles"],
                    "note": f"the timed region is whole compression cycles, at least {args.min_cycles}"},
         "roofline": res["roofline"],

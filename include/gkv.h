@@ -135,6 +135,22 @@ int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*
+ * Device-side step counter, for callers that record the calls once and replay them (HIP
+ * graphs): the host arguments of a recorded launch are frozen, so the step number must come
+ * from device memory.  With a step base set, the `step` argument of every call below is
+ * relative and the kernels use *d_step_base + step.  d_step_base is one int32 of device memory,
+ * the caller's; NULL switches back to absolute steps.  gkv_advance_step_base enqueues
+ * *d_step_base += delta (a one-thread kernel, recordable).  Whenever a call is enqueued or
+ * replayed the base must be a multiple of both w and s (so that ring slots and triggers computed
+ * from the relative step on the host match the device's); advance it by whole compression cycles.
+ * len_max_host stays a host bound: in a recorded steady-state cycle it is b + i for the i-th step.
+ * Every call only launches kernels, so all of them can be recorded; gkv_workspace_init and the
+ * first gkv_evict_static on a device should run before recording starts.
+ */
+gkv_status gkv_set_step_base(gkv_ctx* ctx, const int32_t* d_step_base);
+gkv_status gkv_advance_step_base(gkv_ctx* ctx, int32_t delta, void* stream);
+
+/*
  * Every decode step (paper, Preliminary: the cache the newest token attends to;
  * evicted entries are invisible to later tokens).  For every (layer, sequence),
  * with len = LEN + (step - LEN_STEP) from d_state:

@@ -24,7 +24,7 @@ EXPORTS = [
     "gkv_cache_bytes", "gkv_k_offset", "gkv_set_param", "gkv_attend_decode", "gkv_score_window",
     "gkv_global_update", "gkv_select_topk", "gkv_compact", "gkv_evict", "gkv_profile_enable",
     "gkv_profile_read", "gkv_profile_reset", "gkv_probe_attend_read", "gkv_redundancy_combine", "gkv_evicted_positions", "gkv_pool_scores",
-    "gkv_evict_static",
+    "gkv_evict_static", "gkv_set_step_base", "gkv_advance_step_base",
 ]
 
 
@@ -70,6 +70,8 @@ def load_library():
     lib.gkv_select_topk.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.gkv_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.gkv_evict.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.gkv_set_step_base.argtypes = [vp, vp]
+    lib.gkv_advance_step_base.argtypes = [vp, i32, vp]
     lib.gkv_evict_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.gkv_redundancy_combine.argtypes = [vp, vp, vp, i32, i32, vp, c_float, c_float, c_float, i32, vp, vp, vp, vp]
     lib.gkv_pool_scores.argtypes = [vp, vp, vp, i32, i32, vp, vp]
@@ -142,6 +144,13 @@ class Context:
         n = c_size_t()
         self._check(self.lib.gkv_workspace_bytes(self.h, byref(n)), "gkv_workspace_bytes")
         return n.value
+
+    def set_step_base(self, d_step_base):
+        """d_step_base: int32 device tensor of one element (or None for absolute steps)."""
+        self._check(self.lib.gkv_set_step_base(self.h, _ptr(d_step_base)), "gkv_set_step_base")
+
+    def advance_step_base(self, delta: int):
+        self._check(self.lib.gkv_advance_step_base(self.h, delta, _stream()), "gkv_advance_step_base")
 
     def workspace_init(self, workspace):
         self._check(self.lib.gkv_workspace_init(self.h, _ptr(workspace), _stream()), "gkv_workspace_init")

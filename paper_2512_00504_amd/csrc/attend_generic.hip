@@ -13,6 +13,7 @@ constexpr int NWG = 4;     // wavefronts per workgroup
 // Dynamic LDS, per wavefront: float prob[cap + 1]; float qs[d]
 template <typename T>
 __global__ __launch_bounds__(NWG * 64) void attend_generic_kernel(GkvDims dm, AttendArgs a) {
+  a.step = resolve_step(dm, a.step);
   extern __shared__ float smem[];
   constexpr int EPC = Elem<T>::EPC;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

@@ -200,6 +200,7 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
 // KT = 16-key tiles per wavefront iteration (1 or 2)
 template <int NW, int KT>
 __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
+  a.step = resolve_step(dm, a.step);
   constexpr int KEYS = 16 * KT;             // keys per iteration
   extern __shared__ float smem[];
   __shared__ int s_misc[2];

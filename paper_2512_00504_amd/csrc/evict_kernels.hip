@@ -36,6 +36,7 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
                                                             const float* __restrict__ F_hist,
                                                             const int32_t* __restrict__ d_state, int step,
                                                             float* __restrict__ F_out) {
+  step = resolve_step(dm, step);
   __shared__ float red[8];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const SeqState st = load_state(d_state, lb);
@@ -68,6 +69,7 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
 __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const float* __restrict__ F,
                                                           const int32_t* __restrict__ d_state, int step,
                                                           int32_t* __restrict__ keep_idx) {
+  step = resolve_step(dm, step);
   extern __shared__ uint32_t keys[];
   __shared__ int hist[256];
   __shared__ int tmp[4];
@@ -141,6 +143,7 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
                                                       const float* __restrict__ F, void* K, void* V,
                                                       float* __restrict__ F_hist, int32_t* pos,
                                                       const int32_t* __restrict__ d_state, int step) {
+  step = resolve_step(dm, step);
   extern __shared__ int keep_s[];
   __shared__ int red_i[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
@@ -222,6 +225,7 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
 __global__ __launch_bounds__(256) void pool_scores_kernel(GkvDims dm, const float* __restrict__ F,
                                                           const int32_t* __restrict__ d_state, int step,
                                                           int kernel, float* __restrict__ F_out) {
+  step = resolve_step(dm, step);
   extern __shared__ float fbuf[];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
   const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
@@ -247,6 +251,7 @@ __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, cons
                                                                 const int32_t* __restrict__ pos,
                                                                 const int32_t* __restrict__ d_state, int step,
                                                                 int32_t* __restrict__ evicted) {
+  step = resolve_step(dm, step);
   extern __shared__ uint32_t kept[];
   __shared__ int tmp[4];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
@@ -280,12 +285,15 @@ __global__ __launch_bounds__(256) void evicted_positions_kernel(GkvDims dm, cons
 }
 
 __global__ void finalize_state_kernel(GkvDims dm, int32_t* d_state, int step) {
+  step = resolve_step(dm, step);
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= dm.L * dm.B) return;
   const SeqState st = load_state(d_state, i);
   const int l = compression_length(st, step, dm.b, dm.w, dm.cap);
   if (l > 0) *(int4*)(d_state + 4 * (size_t)i) = make_int4(dm.b, step + 1, dm.b - dm.w, dm.b & ~15);
 }
+
+__global__ void add_int_kernel(int32_t* p, int32_t delta) { *p += delta; }
 
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -338,5 +346,10 @@ hipError_t gkv_launch_evicted_positions(const GkvLaunch& ln, const GkvDims& dm, 
 
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n) {
   hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t gkv_launch_add_int(hipStream_t stream, int32_t* p, int32_t delta) {
+  hipLaunchKernelGGL(add_int_kernel, dim3(1), dim3(1), 0, stream, p, delta);
   return hipGetLastError();
 }

@@ -100,6 +100,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
     d.scale_l2_hi = (float)sl2;
     d.scale_l2_lo = (float)(sl2 - (double)d.scale_l2_hi);
   }
+  d.step_base = nullptr;
   c->esz = cfg->dtype == GKV_F32 ? 4 : 2;
   c->attend_splits = 0;
   c->ws_splits = 1;
@@ -239,6 +240,20 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
   }
   if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
+}
+
+// ---- device-side step counter ----------------------------------------------------------------------
+extern "C" gkv_status gkv_set_step_base(gkv_ctx* ctx, const int32_t* d_step_base) {
+  if (!ctx) return GKV_ERR_INVALID_ARG;
+  ctx->dims.step_base = d_step_base;
+  for (int i = 0; i < ctx->dims.w; ++i) ctx->stats_step[i] = -1;    // recorded steps were counted from another origin
+  return GKV_OK;
+}
+
+extern "C" gkv_status gkv_advance_step_base(gkv_ctx* ctx, int32_t delta, void* stream) {
+  if (!ctx || !ctx->dims.step_base) return GKV_ERR_INVALID_ARG;
+  return gkv_launch_add_int((hipStream_t)stream, const_cast<int32_t*>(ctx->dims.step_base), delta) == hipSuccess
+             ? GKV_OK : GKV_ERR_HIP;
 }
 
 // ---- the five calls -----------------------------------------------------------------------------

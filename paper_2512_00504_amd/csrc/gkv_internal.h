@@ -18,6 +18,9 @@ struct GkvDims {
   // 2 as fma(z, lo, fma(z, hi, -m)), two roundings of a small number and no systematic error
   // from a rounded scale, and the decode and window-score kernels form it the same way
   float scale_l2_hi, scale_l2_lo;
+  // Device-side step counter (null: none).  When set, the `step` argument of a call is relative
+  // and the kernels use *step_base + step, so recorded launches (HIP graphs) can be replayed.
+  const int32_t* step_base;
 };
 
 struct GkvProfile;   // event pools, defined in gkv_api.hip
@@ -101,6 +104,7 @@ hipError_t gkv_launch_pool_scores(const GkvLaunch& ln, const GkvDims& dm, const 
 hipError_t gkv_launch_evicted_positions(const GkvLaunch& ln, const GkvDims& dm, const int32_t* keep_idx,
                                         const int32_t* pos, const int32_t* d_state, int32_t step, int32_t* evicted);
 hipError_t gkv_launch_fill_zero(hipStream_t stream, int32_t* p, size_t n);
+hipError_t gkv_launch_add_int(hipStream_t stream, int32_t* p, int32_t delta);
 
 // Event bracketing for profiling (gkv_api.hip).  Returns the events to pass to
 // hipExtLaunchKernelGGL, or nulls when profiling is off.
@@ -139,6 +143,11 @@ __device__ __forceinline__ SeqState load_state(const int32_t* d_state, int lb) {
 __device__ __forceinline__ int length_before_step(const SeqState& s, int t, int cap) {
   const int l = s.len + (t - s.len_step);
   return l < 0 ? 0 : (l > cap ? cap : l);
+}
+
+// The decode step a kernel works on: its argument, plus the device-side step base if there is one.
+__device__ __forceinline__ int resolve_step(const GkvDims& dm, int step) {
+  return dm.step_base ? step + *dm.step_base : step;
 }
 
 // Whether the compression after decode step `step` applies to this (layer, sequence): its cache

@@ -56,6 +56,7 @@ __device__ __forceinline__ void finish_unit(const GkvDims& dm, const RedArgs& a,
 // Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
 template <typename T>
 __global__ __launch_bounds__(256) void redundancy_generic_kernel(GkvDims dm, RedArgs a) {
+  a.step = resolve_step(dm, a.step);
   extern __shared__ double smem[];
   constexpr int EPC = Elem<T>::EPC;
   const int tid = threadIdx.x, unit = blockIdx.x, lb = unit / dm.Hkv, d = dm.d;
@@ -113,6 +114,7 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
 // C[k, j] = sum_c mfma(A_T[c], A_J[c]) lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
 // Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
 __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
+  a.step = resolve_step(dm, a.step);
   extern __shared__ double smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, kb = lane >> 4;
   const int unit = blockIdx.x, lb = unit / dm.Hkv;

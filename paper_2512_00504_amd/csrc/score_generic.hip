@@ -10,6 +10,7 @@ namespace {
 // Dynamic LDS, per wavefront: float z[cap]; float rowmax[cap]; float sacc[cap]; float qs[d]
 template <typename T>
 __global__ void score_generic_kernel(GkvDims dm, ScoreArgs a) {
+  a.step = resolve_step(dm, a.step);
   extern __shared__ float smem[];
   constexpr int EPC = Elem<T>::EPC;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;

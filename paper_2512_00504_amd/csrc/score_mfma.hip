@@ -60,6 +60,7 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
 // HAVE_STATS: a.stats holds (max, sum) of every window row, recorded by the decode kernel.
 template <int NW, int G, int WT, bool HAVE_STATS>
 __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
+  a.step = resolve_step(dm, a.step);
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kb = lane >> 4;
