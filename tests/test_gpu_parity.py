@@ -134,6 +134,15 @@ def test_cfg3_full_size_sampled_units():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+def test_cfg3_layer_group_launch_as_the_benchmark_times_it():
+    # the benchmark's default splits the 28 layers into two contexts of 14: that launch size
+    # (448 units), layers 14..27 of the trace, oracle on sampled pairs
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=14)
+    pairs = [(0, 0), (0, 7), (6, 2), (13, 0), (13, 7)]
+    st = run_parity(wl, 2 * wl.interval, pairs=pairs, prompts=[wl.budget] * wl.batch, workers=16)
+    assert st["events"] == 2 and st["pair_events"] == 10
+
+
 def test_cfg3_full_size_longer_run():
     # 44 compressions at the benchmark's launch configuration, free-running between them
     wl = CONFIGS["cfg3_28layer_b512"]
