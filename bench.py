@@ -347,6 +347,18 @@ def run_workload(wl, args, n_streams, timed_cycles, warm_cycles, kernel_cycles, 
 
     ceil_group = ceiling(groups[0].K, groups[0].V)
 
+    # the reader's rate against the size of what it re-reads (fresh buffers of the same layout): if the
+    # 256 MB memory-side cache served repeated reads faster than HBM, the small sets would stand out
+    sweep = None
+    if mfma and not args.leg and wl.n_units >= 448:
+        sweep = []
+        for units in (448, 896, 1792, 3584):
+            Kb = torch.ones(units, wl.capacity, wl.head_dim, dtype=dt, device=dev)
+            Vb = torch.ones(units, wl.capacity, wl.head_dim, dtype=dt, device=dev)
+            c = ceiling(Kb, Vb)
+            sweep.append({"working_set_MB": 2 * Kb.numel() * esz / 1e6, "GBps": c["GBps"]})
+            del Kb, Vb
+
     # the same reader on every group's cache at once, each on its group's stream, as the timed
     # region runs the decode kernel: the ceiling for the overlapped launches
     ceil_overlap = None
@@ -424,13 +436,17 @@ def run_workload(wl, args, n_streams, timed_cycles, warm_cycles, kernel_cycles, 
                              "runs the groups on separate streams"},
         "roofline_all_layers_one_launch": full,
         "read_ceiling": {"per_group_launch": ceil_group, "all_layers": ceil_full, "groups_overlapped": ceil_overlap,
-                         "note": "the decode kernel's load pattern with no arithmetic, merge or stores, on the same caches"},
+                         "working_set_sweep": sweep,
+                         "note": "the decode kernel's load pattern with no arithmetic, merge or stores, on the same caches "
+                                 "(the sweep: on fresh buffers of growing size, each re-read 45 times)"},
         "whole_step": {"algorithmic_bytes_per_step": bytes_per_step,
                        "GBps": bytes_per_step * K / wall_s / 1e9,
                        "hbm_frac": bytes_per_step * K / wall_s / 1e9 / HBM_PEAK_GBS,
-                       "cache_assisted": kv_bytes < 2 * (256 << 20),
-                       "note": ("K+V cache of %.0f MB against a 256 MB memory-side cache: part of every step's reads is "
-                                "served from that cache, so this is a rate in algorithmic bytes, not pure HBM traffic"
+                       "fits_memory_side_cache_twice": kv_bytes < 2 * (256 << 20),
+                       "note": ("K+V cache of %.0f MB against a 256 MB memory-side cache: part of a step's reads may be "
+                                "served from that cache, so this is a rate in algorithmic bytes, not proven HBM traffic; "
+                                "see roofline_out_of_cache for a cache more than twice that size, and "
+                                "read_ceiling.working_set_sweep for what the cache does to this access pattern"
                                 % (kv_bytes / 1e6)) if kv_bytes < 2 * (256 << 20) else
                                ("K+V cache of %.0f MB, more than twice the 256 MB memory-side cache" % (kv_bytes / 1e6))},
         "per_kernel": per_kernel,
