@@ -244,6 +244,40 @@ def test_odd_shapes_bf16(shape):
     assert st["events"] >= 3
 
 
+@pytest.mark.parametrize("params", [None, {"force_generic": 1}])
+def test_largest_capacity_prompt_fills_the_cache(params):
+    # b = 3840, s = 96: capacity 3936 rows, the largest the kernels' 64 KiB of LDS admit at d = 128.
+    # Sequence 0 starts with a prompt of b rows, so its first compression sees every row of the
+    # cache in use (l = capacity); sequence 1 starts with 1000 rows and is left alone.
+    wl = CONFIGS["cfg2_single_layer"].with_(n_layers=1, batch=2, budget=3840, interval=96, seed=41)
+    assert wl.capacity == 3936
+    st = run_parity(wl, 96, prompts=[3840, 1000], params=params, chunk=96, say=_say)
+    assert st["pair_events"] == 1
+    ev = st["oracles"][(0, 0)].events[0]
+    assert ev["len"] == 3936 and st["oracles"][(0, 1)].len == 1096
+
+
+@pytest.mark.parametrize("shape", [
+    dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=2, budget=9, window=8, interval=8),       # keeps ONE candidate
+    dict(dtype="bf16", head_dim=128, n_q_heads=8, n_kv_heads=2, budget=17, window=16, interval=16),   # same, matrix cores
+    dict(dtype="bf16", head_dim=128, n_q_heads=4, n_kv_heads=1, budget=64, window=16, interval=32),   # MQA: one KV head
+    dict(dtype="bf16", head_dim=128, n_q_heads=14, n_kv_heads=2, budget=64, window=16, interval=32,
+         alpha=1.0, combine="avg"),                                                                    # no decay: history rows keep F
+])
+def test_degenerate_shapes_and_parameters(shape):
+    kw = dict(n_layers=2, batch=2, n_steps=200, seed=51)
+    kw.update(shape)
+    wl = CONFIGS["cfg2_single_layer"].with_(**kw)
+    st = run_parity(wl, wl.n_steps, chunk=64)
+    assert st["events"] >= 4
+    if shape.get("alpha") == 1.0:          # avg form with alpha = 1: F_t = F_{t-1} for every row with history
+        for orc in st["oracles"].values():
+            ev0, ev1 = orc.events[-2], orc.events[-1]
+            for j in range(wl.n_kv_heads):
+                kept = ev0["F"][j][ev0["keep"][j]]
+                np.testing.assert_array_equal(ev1["F"][j][:ev1["n_hist"]], kept)
+
+
 @pytest.mark.parametrize("params", [None, {"attend_splits": 3}, {"force_generic": 1}])
 def test_results_are_deterministic(params):
     # same inputs, same bits: outputs, kept indices, scores and cache contents of two runs
