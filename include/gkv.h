@@ -131,7 +131,9 @@ int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_
  * a thread of the compaction kernel keeps in flight per round), "score_reuse_stats" (0 = the
  * window score always computes its rows' softmax statistics itself instead of reusing the
  * ones the matrix-core decode kernel recorded during the window's decode steps; see
- * gkv_score_window). */
+ * gkv_score_window), "evict_fuse_global" (1 = gkv_evict computes the global score in the tail
+ * of the matrix-core window-score kernel, S still in LDS, instead of a launch of its own;
+ * same results, measured neither faster nor slower). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*

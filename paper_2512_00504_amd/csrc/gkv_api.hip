@@ -108,6 +108,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   c->force_generic = 0;
   c->reuse_stats = 1;
   c->compact_ppt = 8;
+  c->fuse_global = 0;
   c->stats_step = new (std::nothrow) int32_t[cfg->window];
   if (!c->stats_step) { delete c; return GKV_ERR_INVALID_ARG; }
   for (int i = 0; i < cfg->window; ++i) c->stats_step[i] = -1;
@@ -238,6 +239,7 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     ctx->compact_ppt = value;
     return GKV_OK;
   }
+  if (!strcmp(name, "evict_fuse_global")) { ctx->fuse_global = value != 0; return GKV_OK; }
   if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
 }
@@ -259,7 +261,7 @@ extern "C" gkv_status gkv_advance_step_base(gkv_ctx* ctx, int32_t delta, void* s
 // ---- the five calls -----------------------------------------------------------------------------
 static bool use_mfma_attend(const gkv_ctx* ctx) { return ctx->mfma_ok && !ctx->force_generic; }
 static bool use_mfma_score(const gkv_ctx* ctx) {
-  return ctx->mfma_ok && !ctx->force_generic && gkv_score_mfma_supported(ctx->dims.g, ctx->dims.w);
+  return ctx->mfma_ok && !ctx->force_generic && gkv_score_mfma_supported(ctx->dims.g, ctx->dims.w, ctx->dims.cap);
 }
 static gkv_status check_len(const gkv_ctx* ctx, int32_t len_max_host, bool appending) {
   if (len_max_host < 0) return GKV_ERR_INVALID_ARG;
@@ -324,7 +326,7 @@ extern "C" gkv_status gkv_score_window(gkv_ctx* ctx, const void* qwin, const voi
   if (!ctx || !qwin || !K || !d_state || !S || step < 0) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  ScoreArgs a{qwin, K, d_state, step, S, nullptr};
+  ScoreArgs a{qwin, K, d_state, step, S, nullptr, nullptr, nullptr};
   GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
   if (use_mfma_score(ctx)) {
     // Under the causal reading of Eq. 1 a window row's softmax runs over exactly the keys its
@@ -374,10 +376,19 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
   if (F == F_hist) return GKV_ERR_INVALID_ARG;
   gkv_status st = check_len(ctx, len_max_host, false);
   if (st != GKV_OK) return st;
-  st = gkv_score_window(ctx, qwin, K, d_state, step, len_max_host, S, workspace, stream);
-  if (st != GKV_OK) return st;
-  st = gkv_global_update(ctx, S, F_hist, d_state, step, len_max_host, F, stream);
-  if (st != GKV_OK) return st;
+  if (ctx->fuse_global && use_mfma_score(ctx)) {
+    // local and global score in one launch: the score kernel keeps S in LDS and finishes with the update
+    ScoreArgs a{qwin, K, d_state, step, S, nullptr, F_hist, F};
+    if (stats_cover_window(ctx, step, workspace, K, qwin)) a.stats = gkv_carve_workspace(ctx, workspace).stats;
+    GkvLaunch ln{ctx, GKV_K_SCORE, (hipStream_t)stream};
+    st = hip_status(gkv_launch_score_mfma(ln, ctx->dims, a));
+    if (st != GKV_OK) return st;
+  } else {
+    st = gkv_score_window(ctx, qwin, K, d_state, step, len_max_host, S, workspace, stream);
+    if (st != GKV_OK) return st;
+    st = gkv_global_update(ctx, S, F_hist, d_state, step, len_max_host, F, stream);
+    if (st != GKV_OK) return st;
+  }
   st = gkv_select_topk(ctx, F, d_state, step, len_max_host, keep_idx, workspace, stream);
   if (st != GKV_OK) return st;
   return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace, stream);

@@ -33,6 +33,7 @@ struct gkv_ctx {
   int32_t ws_splits;      // split count the workspace was sized for by gkv_workspace_bytes (1 = no partials)
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
+  int32_t fuse_global;    // gkv_evict: global score in the tail of the window-score kernel
   int32_t compact_ppt;    // 16-byte pieces per thread and chunk round of the compaction kernel: 4, 8 or 16
   int32_t reuse_stats;    // window score may reuse the softmax statistics the decode kernel recorded
   bool mfma_ok;           // bf16, d == 128, g <= 16
@@ -84,10 +85,11 @@ hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const 
 struct ScoreArgs {
   const void* qwin; const void* K; const int32_t* d_state; int32_t step; float* S;
   const float2* stats;   // softmax statistics of the window's decode steps, or null: compute them
+  const float* F_hist; float* F_out;   // non-null F_out: also the global score (matrix-core kernel only)
 };
 hipError_t gkv_launch_score_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const ScoreArgs& a);
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a);
-bool gkv_score_mfma_supported(int g, int w);
+bool gkv_score_mfma_supported(int g, int w, int cap);
 
 hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, const float* S,
                                     const float* F_hist, const int32_t* d_state, int32_t step, float* F_out);

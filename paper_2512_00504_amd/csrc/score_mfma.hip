@@ -55,8 +55,8 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
   for (int c = 0; c < 4; ++c) kA[c] = ld16(p + c * step_off);
 }
 
-// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; and, when the row statistics
-// are computed here, float redM[NW*G*w]; float redS[NW*G*w]
+// Dynamic LDS: char qs[G*w*QSTR]; float rowM[G*w]; float rowZ[G*w]; float sbuf[cap]; float red[8]; and,
+// when the row statistics are computed here, float redM[NW*G*w]; float redS[NW*G*w]
 // HAVE_STATS: a.stats holds (max, sum) of every window row, recorded by the decode kernel.
 template <int NW, int G, int WT, bool HAVE_STATS>
 __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreArgs a) {
@@ -77,6 +77,8 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   char* qs = smem_raw;
   float* rowM = (float*)(qs + ROWS * QSTR);
   float* rowZ = rowM + ROWS;
+  float* sbuf = rowZ + ROWS;                // S of this unit, for the fused global-score tail
+  float* red = sbuf + cap;
 
   // stage the window queries: LDS row h*W + k holds head h, window row k (k-th oldest)
   for (int x = tid; x < ROWS * 16; x += NW * 64) {
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     // ---- pass 1: row max and row sum over the keys visible to each window row -----------------
     // Only the last tiles (those reaching into the window) need the causal mask; the running sum
     // is rescaled only when some lane's maximum moved.
-    float* redM = rowZ + ROWS;
+    float* redM = red + 8;
     float* redS = redM + NW * ROWS;
     const int n_tiles = (l + 15) >> 4;
 #pragma unroll
@@ -224,7 +226,29 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
       v += __shfl_xor(v, 4);
       v += __shfl_xor(v, 8);
       const int key = 16 * T + 4 * kb + e;
-      if (r == 0 && key < cc) So[key] = v / wf;
+      if (r == 0 && key < cc) { const float sv = v / wf; So[key] = sv; sbuf[key] = sv; }
+    }
+  }
+
+  // ---- optional tail: global score of the candidates (Section 4), S still in LDS ---------------
+  if (a.F_out != nullptr) {
+    __syncthreads();
+    float mx = 0.f;
+    for (int n = tid; n < cc; n += NW * 64) mx = fmaxf(mx, sbuf[n]);
+    mx = block_max(mx, red);
+    const int n_hist = seq.n_hist < 0 ? 0 : (seq.n_hist > cc ? cc : seq.n_hist);
+    const float* Hu = a.F_hist + (size_t)unit * cap;
+    float* Fu = a.F_out + (size_t)unit * cap;
+    for (int n = tid; n < cc; n += NW * 64) {
+      const float sn = mx > 0.f ? sbuf[n] / mx : 0.f;
+      float f = sn;
+      if (n < n_hist) {
+        const float h = dm.alpha * Hu[n];
+        f = dm.combine == GKV_COMBINE_MAX ? fmaxf(h, sn)
+          : dm.combine == GKV_COMBINE_AVG ? h + (1.f - dm.alpha) * sn
+                                          : h + sn;
+      }
+      Fu[n] = f;
     }
   }
 }
@@ -235,20 +259,20 @@ hipError_t launch(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {
   constexpr int ROWS = G * 16 * WT;
   const int units = dm.L * dm.B * dm.Hkv;
   if (a.stats) {
-    const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * 2 * ROWS;
+    const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + dm.cap + 8);
     return gkv_launch(ln, score_mfma_kernel<NW, G, WT, true>, dim3(units), dim3(NW * 64), shmem, dm, a);
   }
-  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + 2 * NW * ROWS);
+  const size_t shmem = (size_t)ROWS * QSTR + sizeof(float) * (2 * ROWS + dm.cap + 8 + 2 * NW * ROWS);
   return gkv_launch(ln, score_mfma_kernel<NW, G, WT, false>, dim3(units), dim3(NW * 64), shmem, dm, a);
 }
 
 }  // namespace
 
-bool gkv_score_mfma_supported(int g, int w) {
+bool gkv_score_mfma_supported(int g, int w, int cap) {
   const bool g_ok = (g == 1 || g == 2 || g == 4 || g == 5 || g == 7 || g == 8);
   if (!g_ok || (w != 16 && w != 32)) return false;
   const size_t rows = (size_t)g * w;                      // LDS the kernel needs; 64 KiB available
-  return rows * QSTR + sizeof(float) * (2 * rows + 2 * GKV_SCORE_NW * rows) <= 65536;
+  return rows * QSTR + sizeof(float) * (2 * rows + 2 * GKV_SCORE_NW * rows + cap + 8) <= 65536;
 }
 
 hipError_t gkv_launch_score_mfma(const GkvLaunch& ln, const GkvDims& dm, const ScoreArgs& a) {

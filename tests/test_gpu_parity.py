@@ -84,6 +84,17 @@ def test_cfg3_shape_evict_entry_point(form):
     assert st["events"] == 4
 
 
+def test_cfg3_shape_evict_with_the_global_score_in_the_score_kernels_tail():
+    # optional one-launch local + global score (S stays in LDS for the update): same results
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
+    st = run_parity(wl, 1024, fused_evict=True, params={"evict_fuse_global": 1}, check_state_every_event=False)
+    assert st["events"] == 4
+    wl5 = CONFIGS["cfg5_large_batch"].with_(n_layers=1, batch=2)
+    st = run_parity(wl5, 1216, fused_evict=True, params={"evict_fuse_global": 1, "score_reuse_stats": 0},
+                    check_state_every_event=False)
+    assert st["events"] == 3
+
+
 def test_cfg3_shape_32_key_slices():
     # the other slice size of the matrix-core attend kernel
     wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
