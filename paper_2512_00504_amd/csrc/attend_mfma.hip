@@ -199,7 +199,7 @@ __device__ __forceinline__ void process_slice(Slice<KT>& s, Running& st, const b
 
 // KT = 16-key tiles per wavefront iteration (1 or 2)
 template <int NW, int KT>
-__global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
+__global__ __launch_bounds__(NW * 64, (KT == 1 && NW <= 8) ? 4 : 2) void attend_mfma_kernel(GkvDims dm, AttendArgs a) {
   a.step = resolve_step(dm, a.step);
   constexpr int KEYS = 16 * KT;             // keys per iteration
   extern __shared__ float smem[];
@@ -398,11 +398,17 @@ __global__ __launch_bounds__(NW * 64, KT == 1 ? 4 : 2) void attend_mfma_kernel(G
 
 }  // namespace
 
-hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a) {
-  constexpr int NW = 4;
+template <int NW>
+static hipError_t launch_attend(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a) {
   const int units = dm.L * dm.B * dm.Hkv;
   const size_t shmem = sizeof(float) * (NW * dm.g * OSTR + NW * 16 + NW * 16) + (32 + 16 * dm.g) * 16;
-  if (a.tile_keys == 32)
-    return gkv_launch(ln, attend_mfma_kernel<NW, 2>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
+  if (a.tile_keys == 32 && NW == 4)
+    return gkv_launch(ln, attend_mfma_kernel<4, 2>, dim3(units * a.splits), dim3(4 * 64), shmem, dm, a);
   return gkv_launch(ln, attend_mfma_kernel<NW, 1>, dim3(units * a.splits), dim3(NW * 64), shmem, dm, a);
+}
+
+hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a) {
+  if (a.waves == 16) return launch_attend<16>(ln, dm, a);
+  if (a.waves == 8) return launch_attend<8>(ln, dm, a);
+  return launch_attend<4>(ln, dm, a);
 }

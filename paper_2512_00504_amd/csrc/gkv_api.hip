@@ -109,6 +109,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   c->reuse_stats = 1;
   c->compact_ppt = 8;
   c->fuse_global = 0;
+  c->attend_waves = 0;
   c->stats_step = new (std::nothrow) int32_t[cfg->window];
   if (!c->stats_step) { delete c; return GKV_ERR_INVALID_ARG; }
   for (int i = 0; i < cfg->window; ++i) c->stats_step[i] = -1;
@@ -239,6 +240,12 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     ctx->compact_ppt = value;
     return GKV_OK;
   }
+  if (!strcmp(name, "attend_waves")) {
+    if (value != 0 && value != 4 && value != 8 && value != 16) return GKV_ERR_INVALID_ARG;
+    if (value * ctx->dims.g * 132 * 4 + value * 128 + (32 + 16 * ctx->dims.g) * 16 > 65000) return GKV_ERR_SHAPE;
+    ctx->attend_waves = value;
+    return GKV_OK;
+  }
   if (!strcmp(name, "evict_fuse_global")) { ctx->fuse_global = value != 0; return GKV_OK; }
   if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
@@ -301,7 +308,7 @@ extern "C" gkv_status gkv_attend_decode(gkv_ctx* ctx, const void* q, const void*
   gkv_status st = check_len(ctx, len_max_host, k_new != nullptr);
   if (st != GKV_OK) return st;
   AttendArgs a{q, k_new, v_new, K, V, pos, step, qwin, d_state, out, gkv_carve_workspace(ctx, workspace), 1,
-               ctx->attend_tile, 1, 0};
+               ctx->attend_tile, 1, 0, ctx->attend_waves > 0 ? ctx->attend_waves : 4};
   {
     const size_t slot_bytes = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hq * ctx->dims.d * ctx->esz;
     a.copy_q = (const char*)q != (const char*)qwin + (size_t)(step % ctx->dims.w) * slot_bytes;

@@ -33,6 +33,7 @@ struct gkv_ctx {
   int32_t ws_splits;      // split count the workspace was sized for by gkv_workspace_bytes (1 = no partials)
   int32_t attend_tile;    // keys per wavefront iteration of the matrix-core attend kernel: 16 or 32
   int32_t force_generic;
+  int32_t attend_waves;   // 0 = automatic
   int32_t fuse_global;    // gkv_evict: global score in the tail of the window-score kernel
   int32_t compact_ppt;    // 16-byte pieces per thread and chunk round of the compaction kernel: 4, 8 or 16
   int32_t reuse_stats;    // window score may reuse the softmax statistics the decode kernel recorded
@@ -78,6 +79,7 @@ struct AttendArgs {
   GkvWorkspace ws; int32_t splits; int32_t tile_keys;
   int32_t copy_q;   // 0 when q already is the ring slot of this step
   int32_t write_stats;   // record (max, sum) of every query head's softmax in ws.stats
+  int32_t waves;         // wavefronts per workgroup of the matrix-core kernel: 4, 8 or 16
 };
 hipError_t gkv_launch_attend_generic(const GkvLaunch& ln, const GkvDims& dm, int dtype, const AttendArgs& a);
 hipError_t gkv_launch_attend_mfma(const GkvLaunch& ln, const GkvDims& dm, const AttendArgs& a);

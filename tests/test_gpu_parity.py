@@ -134,6 +134,14 @@ def test_window_score_with_and_without_recorded_statistics_agree():
         np.testing.assert_allclose(a, b, rtol=3e-6, atol=1e-30)
 
 
+@pytest.mark.parametrize("waves", [8, 16])
+def test_cfg3_shape_more_wavefronts_per_unit(waves):
+    # the matrix-core attend kernel with 8 or 16 wavefronts per workgroup instead of 4
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
+    st = run_parity(wl, 768, params={"attend_waves": waves}, check_state_every_event=False)
+    assert st["events"] == 2
+
+
 def test_cfg3_full_size_sampled_units():
     # the launch configuration the benchmark times: all 896 units on the GPU, the oracle on a
     # sample of (layer, sequence) pairs that covers first/last layer and sequence
