@@ -46,6 +46,8 @@
  *     (N_TILED = budget rounded down to 16).  A row-major K cache with
  *     N_TILED = 0 is a valid state.  gkv_k_offset() returns the offset.
  *     V is plain row-major [capacity, d].
+ *   - A context keeps host-side bookkeeping (tuning knobs, which ring slots hold recorded
+ *     softmax statistics): use it from one thread at a time, one context per set of buffers.
  *   - Return value: GKV_OK or an error code; arguments are validated on the
  *     host before anything is enqueued, a failed call enqueues nothing.
  *     Results are deterministic: same inputs, same bits.
