@@ -129,7 +129,7 @@ int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_
 /* Tuning knobs (host only): "attend_splits" (workgroups per unit in the matrix-core
  * attend kernel; 0 = default = 1; set it before gkv_workspace_bytes), "attend_tile" (16 or 32 keys per wavefront iteration of
  * the matrix-core attend kernel), "attend_waves" (4, 8 or 16 wavefronts per workgroup of that
- * kernel; 0 = default = 4), "force_generic" (1 = use the plain vector-ALU
+ * kernel; 0 = default: 8 for launches of at most 256 units, else 4), "force_generic" (1 = use the plain vector-ALU
  * kernels even where matrix-core kernels exist), "compact_ppt" (4, 8 or 16: 16-byte pieces
  * a thread of the compaction kernel keeps in flight per round), "score_reuse_stats" (0 = the
  * window score always computes its rows' softmax statistics itself instead of reusing the
