@@ -276,7 +276,8 @@ gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_
  * hipMalloc.  Same compression, same results in K, V, F_hist, pos and d_state; the local score,
  * the global score and the kept indices live in a fixed array of GKV_STATIC_SCRATCH_BYTES bytes
  * that is part of the library's device image (every GPU the library runs on holds it until the
- * process ends).  The call allocates and frees nothing.  It needs
+ * process ends).  The call allocates and frees nothing (as long as the benchmark timing hooks of
+ * gkv_bench.h are off, which they are unless switched on).  It needs
  *   2 * align256(4 * L*B*h_kv * capacity) + align256(4 * L*B*h_kv * (b - w))
  * bytes and returns GKV_ERR_SCRATCH, enqueuing nothing, if that exceeds the array (the 28-layer,
  * batch-8, b = 512 shape needs 6.4 MB).  The device of `stream` must be the current device.
