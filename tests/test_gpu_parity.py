@@ -248,6 +248,23 @@ def test_cfg5_shape_heavy_tailed_keys():
     _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
 
 
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_cfg3_shape_other_seeds(seed):
+    # other draws of the same recipe: other tie patterns, other burst alignments
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=1, batch=2, seed=seed)
+    st = run_parity(wl, 1280, check_state_every_event=False)
+    assert st["events"] == 6
+
+
+def test_cfg5_shape_many_events_heavy_tails():
+    # ten compressions of one sequence with Student-t keys: probabilities far below fp32's range
+    # compete in the top-k (the tolerated-swap rule's second clause), free-running between events
+    wl = CONFIGS["cfg5_large_batch"].with_(n_layers=1, batch=1, seed=77)
+    st = run_parity(wl, 1024 + 10 * 64, check_state_every_event=False, chunk=64)
+    assert st["events"] == 10
+    _say(f"  max out err {st['max_out_err']:.2e} swaps {st['swaps']}")
+
+
 @pytest.mark.parametrize("shape", [
     dict(n_q_heads=4, n_kv_heads=4, budget=96, window=16, interval=32),          # MHA, g = 1
     dict(n_q_heads=16, n_kv_heads=2, budget=100, window=16, interval=40),        # g = 8, b and s not multiples of 16, w does not divide s

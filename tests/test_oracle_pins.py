@@ -227,6 +227,28 @@ def test_select_topk_ties_scale_and_permutation():
     assert sorted(perm[kept_perm].tolist()) == keep.tolist()
 
 
+def test_select_topk_and_pool_scores_random_properties():
+    # seeded sweep over shapes and tie densities: the kept set is exactly the k best under
+    # (score descending, index ascending), i.e. every kept entry beats every dropped one
+    rng = np.random.default_rng(80)
+    for trial in range(60):
+        c = int(rng.integers(2, 70)); k = int(rng.integers(1, c)); h = int(rng.integers(1, 4))
+        F = np.round(rng.standard_normal((h, c)), int(rng.integers(0, 4)))
+        keep = O.select_topk(F, k)
+        assert keep.shape == (h, k) and (np.diff(keep, axis=1) > 0).all()
+        for j in range(h):
+            kept = set(keep[j].tolist())
+            worst_kept = max(kept, key=lambda n: (-F[j, n], n))            # last in the ranking among the kept
+            for n in range(c):
+                if n not in kept:
+                    assert _beats(F[j], worst_kept, n)
+        half = int(rng.integers(0, 5))
+        P = O.pool_scores(F, 2 * half + 1)
+        for j in range(h):
+            for n in range(c):
+                assert P[j, n] == F[j, max(0, n - half):n + half + 1].max()
+
+
 # ---------------------------------------------------- the whole state machine
 def _run(cfg, n_steps, cls=O.OracleA, **kw):
     tr = Trace(cfg)
