@@ -153,20 +153,23 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   const double tau = (double)a.tau;
   for (int J0 = wave * NC; J0 < n_tiles; J0 += 4 * NC) {
     u32x4 colA[NC][4];
-    double inv_j[NC];
+    double inv_j[NC], thr[NC];
     double col[NC];
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
       const int J = min(J0 + cc, n_tiles - 1);            // a clamped duplicate is computed and dropped
       load_k_tile(colA[cc], Kh, J, st.n_tiled, lane, r, kb);
       inv_j[cc] = inv[16 * J + r];
+      // C = dot * inv_k * inv_j >= tau  <=>  dot * inv_k >= tau / inv_j: one product per entry, the
+      // column's factor applied once to the sum (columns >= l have inv_j = 0 and are dropped below)
+      thr[cc] = inv_j[cc] > 0.0 ? tau / inv_j[cc] : 1e300;
       col[cc] = 0.0;
     }
     for (int T = 0; T < n_tiles; ++T) {
       u32x4 rowA[4];
       load_k_tile(rowA, Kh, T, st.n_tiled, lane, r, kb);
       const int k0 = 16 * T + 4 * kb;
-      double invk[4];                                    // rows >= l have inv = 0
+      double invk[4];                                    // rows >= l have inv = 0: their terms are 0 or fail the test
 #pragma unroll
       for (int e = 0; e < 4; ++e) invk[e] = inv[k0 + e];
 #pragma unroll
@@ -176,11 +179,13 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
         for (int c = 0; c < 4; ++c)
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rowA[c]),
                                                         __builtin_bit_cast(bf16x8, colA[cc][c]), acc, 0, 0, 0);
-        const int j = 16 * (J0 + cc) + r;
+        const bool diag_tile = T == J0 + cc;             // wavefront-uniform: only this tile holds k == j
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const double cv = (double)acc[e] * invk[e] * inv_j[cc];
-          if (cv >= tau && k0 + e != j && k0 + e < l) col[cc] += cv;
+          const double t = (double)acc[e] * invk[e];
+          bool pass = t >= thr[cc];
+          if (diag_tile) pass = pass && (4 * kb + e != r);
+          col[cc] += pass ? t : 0.0;
         }
       }
     }
@@ -190,7 +195,7 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       v += __shfl_xor(v, 16);
       v += __shfl_xor(v, 32);
       const int j = 16 * (J0 + cc) + r;
-      if (kb == 0 && J0 + cc < n_tiles && j < l) cs[j] = j < first_recent ? v : 0.0;
+      if (kb == 0 && J0 + cc < n_tiles && j < l) cs[j] = j < first_recent ? v * inv_j[cc] : 0.0;
     }
   }
   __syncthreads();
