@@ -20,11 +20,16 @@ struct RedArgs {
 };
 
 // Precision.  A column sum adds up to l cosines and reaches the hundreds, R' = exp(col - max col)
-// is compared at 1e-5 relative, and the threshold turns each cosine into a yes/no.  So the
-// reciprocal norms are formed in fp64 (a per-row fp32 rounding would be a systematic error of
-// col_j * 1e-7 in every column), each cosine is the dot product (fp32 accumulation of exact
-// bf16 products on the matrix cores, fp64 in the plain kernel) times the two fp64 reciprocal
-// norms, the threshold compares that fp64 value, the column sums and exp(col - max) are fp64.
+// is compared at 1e-5 relative, and the threshold turns each cosine into a yes/no.  The
+// reciprocal norms are formed in fp64.  A column's own norm is a common factor of its whole sum,
+// so it is applied once, in fp64, to the finished sum and folded into the threshold (C >= tau
+// <=> dot * inv_k >= tau / inv_j); a per-entry fp32 rounding of it would be a systematic error of
+// col_j * 1e-7.  What is left per entry in the matrix-core kernel is dot * inv_k in fp32 (dot:
+// fp32 accumulation of exact bf16 products; inv_k: the fp64 value rounded once): its error is a
+// few 1e-8 of the cosine, random from entry to entry, far inside the 1e-6 band in which a
+// threshold decision may legitimately differ from fp64, and it averages out in the sums.  Sums
+// run in fp32 over a lane's four entries of a tile pair and in fp64 from there on; exp(col - max)
+// is fp64.  The plain kernel does everything in fp64.
 __device__ __forceinline__ double block_max_f64(double v, double* red) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
@@ -153,7 +158,8 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   const double tau = (double)a.tau;
   for (int J0 = wave * NC; J0 < n_tiles; J0 += 4 * NC) {
     u32x4 colA[NC][4];
-    double inv_j[NC], thr[NC];
+    double inv_j[NC];
+    float thr[NC];
     double col[NC];
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
@@ -162,16 +168,19 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       inv_j[cc] = inv[16 * J + r];
       // C = dot * inv_k * inv_j >= tau  <=>  dot * inv_k >= tau / inv_j: one product per entry, the
       // column's factor applied once to the sum (columns >= l have inv_j = 0 and are dropped below)
-      thr[cc] = inv_j[cc] > 0.0 ? tau / inv_j[cc] : 1e300;
+      thr[cc] = inv_j[cc] > 0.0 ? (float)(tau / inv_j[cc]) : 3e38f;
       col[cc] = 0.0;
     }
+    u32x4 rowA[4], rowN[4];
+    load_k_tile(rowA, Kh, 0, st.n_tiled, lane, r, kb);
     for (int T = 0; T < n_tiles; ++T) {
-      u32x4 rowA[4];
-      load_k_tile(rowA, Kh, T, st.n_tiled, lane, r, kb);
+      // the next row tile is requested before this one is used: the tiles come from L2, and with
+      // four wavefronts per unit nothing else would cover that latency
+      if (T + 1 < n_tiles) load_k_tile(rowN, Kh, T + 1, st.n_tiled, lane, r, kb);
       const int k0 = 16 * T + 4 * kb;
-      double invk[4];                                    // rows >= l have inv = 0: their terms are 0 or fail the test
+      float invk[4];                                     // rows >= l have inv = 0: their terms are 0 or fail the test
 #pragma unroll
-      for (int e = 0; e < 4; ++e) invk[e] = inv[k0 + e];
+      for (int e = 0; e < 4; ++e) invk[e] = (float)inv[k0 + e];
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -180,14 +189,18 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rowA[c]),
                                                         __builtin_bit_cast(bf16x8, colA[cc][c]), acc, 0, 0, 0);
         const bool diag_tile = T == J0 + cc;             // wavefront-uniform: only this tile holds k == j
+        float part = 0.f;                               // the four entries of this lane, then fp64 across tiles
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const double t = (double)acc[e] * invk[e];
+          const float t = acc[e] * invk[e];
           bool pass = t >= thr[cc];
           if (diag_tile) pass = pass && (4 * kb + e != r);
-          col[cc] += pass ? t : 0.0;
+          part += pass ? t : 0.f;
         }
+        col[cc] += (double)part;
       }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) rowA[c] = rowN[c];
     }
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
