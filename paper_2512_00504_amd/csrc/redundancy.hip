@@ -7,6 +7,7 @@
 // One workgroup per unit.  The l x l x d contraction runs on the matrix cores for bf16, d = 128;
 // a plain vector-ALU kernel covers every other dtype / shape.
 #include "gkv_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -114,14 +115,16 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
   for (int c = 0; c < 4; ++c) kA[c] = *(const u32x4*)(p + c * step_off);
 }
 
-// A wavefront owns column tiles J = wave, wave+4, ...; for each it walks all row tiles T.  The
+// A wavefront owns a contiguous quarter of the column tiles; for each group of them it walks all
+// row tiles T.  The
 // A operand of a tile (lane = key + 16*kblock, 8 channels) is also a valid B operand, so
 // C[k, j] = sum_c mfma(A_T[c], A_J[c]) lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
 // Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
 __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
   a.step = resolve_step(dm, a.step);
   extern __shared__ double smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, kb = lane >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, kb = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int unit = blockIdx.x, lb = unit / dm.Hkv;
   double* cs = (double*)smem;
   double* red = cs + dm.cap;
@@ -152,11 +155,14 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   }
   __syncthreads();
 
-  // NC column tiles per wavefront pass, so that each row tile fetched (from L2) is used NC times
-  constexpr int NC = 4;
+  // Each wavefront owns a contiguous share of the column tiles and takes NC of them per pass, so that
+  // each row tile fetched (from L2) is used NC times.
+  constexpr int NC = 5;
   const int first_recent = l - a.n_recent;
   const double tau = (double)a.tau;
-  for (int J0 = wave * NC; J0 < n_tiles; J0 += 4 * NC) {
+  const int per_wave = (n_tiles + 3) >> 2;
+  const int J_end = min(n_tiles, (wave + 1) * per_wave);
+  for (int J0 = wave * per_wave; J0 < J_end; J0 += NC) {
     u32x4 colA[NC][4];
     double inv_j[NC];
     float thr[NC];
@@ -171,12 +177,10 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       thr[cc] = inv_j[cc] > 0.0 ? (float)(tau / inv_j[cc]) : 3e38f;
       col[cc] = 0.0;
     }
-    u32x4 rowA[4], rowN[4];
-    load_k_tile(rowA, Kh, 0, st.n_tiled, lane, r, kb);
-    for (int T = 0; T < n_tiles; ++T) {
-      // the next row tile is requested before this one is used: the tiles come from L2, and with
-      // four wavefronts per unit nothing else would cover that latency
-      if (T + 1 < n_tiles) load_k_tile(rowN, Kh, T + 1, st.n_tiled, lane, r, kb);
+    // One row tile against the NC column tiles.  DIAG: this row tile is one of the column tiles, so
+    // the entries with k == j are left out (wavefront-uniform, so the common case carries no test).
+    auto row_tile = [&](const u32x4 (&rowA)[4], int T, auto diag) {
+      constexpr bool DIAG = decltype(diag)::value;
       const int k0 = 16 * T + 4 * kb;
       float invk[4];                                     // rows >= l have inv = 0: their terms are 0 or fail the test
 #pragma unroll
@@ -188,19 +192,39 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
         for (int c = 0; c < 4; ++c)
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rowA[c]),
                                                         __builtin_bit_cast(bf16x8, colA[cc][c]), acc, 0, 0, 0);
-        const bool diag_tile = T == J0 + cc;             // wavefront-uniform: only this tile holds k == j
         float part = 0.f;                               // the four entries of this lane, then fp64 across tiles
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float t = acc[e] * invk[e];
           bool pass = t >= thr[cc];
-          if (diag_tile) pass = pass && (4 * kb + e != r);
+          if (DIAG) pass = pass && !(T == J0 + cc && 4 * kb + e == r);
           part += pass ? t : 0.f;
         }
         col[cc] += (double)part;
       }
+    };
+    auto row_tile_any = [&](const u32x4 (&rowA)[4], int T) {
+      if (T >= J0 && T < J0 + NC) row_tile(rowA, T, std::true_type{});
+      else row_tile(rowA, T, std::false_type{});
+    };
+    // Two row-tile buffers in turn: the next tile is requested before the current one is used (the
+    // tiles come from L2, and with four wavefronts per unit nothing else would cover that latency).
+    u32x4 rowA[4], rowB[4];
+    load_k_tile(rowA, Kh, 0, st.n_tiled, lane, r, kb);
+    // The column tiles are complete before the loop starts, so that the loop waits only for its own
+    // row tiles (the memory counter is in order: a wait for a column tile inside the loop would also
+    // wait for the row tile requested just before it).
 #pragma unroll
-      for (int c = 0; c < 4; ++c) rowA[c] = rowN[c];
+    for (int cc = 0; cc < NC; ++cc)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(colA[cc][c]));
+    // (requests past the last tile are clamped, not skipped: with the same number of requests in
+    // flight on every path, the wait for the current tile leaves the next one in flight)
+    for (int T = 0; T < n_tiles; T += 2) {
+      load_k_tile(rowB, Kh, min(T + 1, n_tiles - 1), st.n_tiled, lane, r, kb);
+      row_tile_any(rowA, T);
+      load_k_tile(rowA, Kh, min(T + 2, n_tiles - 1), st.n_tiled, lane, r, kb);
+      if (T + 1 < n_tiles) row_tile_any(rowB, T + 1);
     }
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
@@ -208,7 +232,7 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       v += __shfl_xor(v, 16);
       v += __shfl_xor(v, 32);
       const int j = 16 * (J0 + cc) + r;
-      if (kb == 0 && J0 + cc < n_tiles && j < l) cs[j] = j < first_recent ? v * inv_j[cc] : 0.0;
+      if (kb == 0 && J0 + cc < J_end && j < l) cs[j] = j < first_recent ? v * inv_j[cc] : 0.0;
     }
   }
   __syncthreads();
