@@ -75,6 +75,9 @@ size_t gkv_max_lds_bytes(const gkv_config* c) {
   upd(4 * (3 * cap + d));                                           // score_generic: at least one wavefront's float[3 cap + d]
   upd(4 * cap + 1024 + 64);                                         // select_topk: keys[cap] + histogram + scan scratch
   upd(16 * cap + 32);                                               // redundancy: double cs[cap], red[4], inv[cap]
+  // (the matrix-core redundancy kernel adds a 32 KiB ring of row tiles and asks for the larger
+  // per-workgroup allowance itself when that passes 64 KiB: at the largest capacity it needs 96 KiB
+  // of the 160 KiB a compute unit holds)
   upd(4 * cap + 64);                                                // pooled score / eviction log
   if (c->dtype == GKV_BF16 && d == 128 && g <= 16)
     upd(4 * (4 * g * 132 + 128) + (32 + 16 * g) * 16 + 16);         // attend_mfma: partial outputs + staged rows

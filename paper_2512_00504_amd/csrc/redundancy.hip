@@ -115,11 +115,22 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
   for (int c = 0; c < 4; ++c) kA[c] = *(const u32x4*)(p + c * step_off);
 }
 
-// A wavefront owns a contiguous quarter of the column tiles; for each group of them it walks all
-// row tiles T.  The
-// A operand of a tile (lane = key + 16*kblock, 8 channels) is also a valid B operand, so
-// C[k, j] = sum_c mfma(A_T[c], A_J[c]) lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
-// Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]
+// A wavefront owns a contiguous quarter of the column tiles and holds NC of them in registers per
+// pass; in each pass the workgroup walks all row tiles T together.  The A operand of a tile
+// (lane = key + 16*kblock, 8 channels) is also a valid B operand, so C[k, j] = sum_c mfma(A_T[c], A_J[c])
+// lands as lane (j = lane%16, blk): rows k = 16T + 4 blk + e.
+//
+// Row tiles reach the wavefronts through LDS: every wavefront needs every row tile in every pass,
+// and if each fetched them itself a unit's keys (l * 256 bytes) would be read 4 * passes times; the
+// units resident on one XCD together exceed its L2, so those re-reads would come from memory and
+// bound the kernel.  Instead the workgroup moves through the row tiles in groups of four: each
+// wavefront fetches one tile of the next group while all four work on the current group, stores it
+// into the other half of a two-group ring, and one barrier per group hands the ring over.
+//
+// Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]; then the ring, 2 groups x 4 tiles x 4 KiB
+constexpr int RED_NC = 5;
+constexpr int RED_RING_BYTES = 2 * 4 * TILE_BYTES;
+
 __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
   a.step = resolve_step(dm, a.step);
   extern __shared__ double smem[];
@@ -129,40 +140,65 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   double* cs = (double*)smem;
   double* red = cs + dm.cap;
   double* inv = red + 4;
+  char* ring = (char*)(inv + dm.cap);
   const SeqState st = load_state(a.d_state, lb);
   const int l = compression_length(st, a.step, dm.b, dm.w, dm.cap);
   if (l == 0) return;
   const char* Kh = (const char*)a.K + (size_t)unit * dm.cap * ROW_BYTES;
   const int n_tiles = (l + 15) >> 4;
 
-  // row norms: a quarter-wave per row, 16 bytes per lane
-  for (int n = tid >> 4; n < n_tiles * 16; n += 16) {
-    double ss = 0.0;
-    if (n < l) {
-      const int ch = tid & 15;
-      const char* p = (n < st.n_tiled) ? Kh + (size_t)(n >> 4) * TILE_BYTES + ch * 256 + (n & 15) * 16
-                                       : Kh + (size_t)n * ROW_BYTES + ch * 16;
-      const u32x4 v = *(const u32x4*)p;
+  // Row norms.  Squared norms first, a quarter-wave per row and 16 bytes per lane, eight rows' loads
+  // issued together; then one row per thread for the fp64 square root and reciprocal, which cost
+  // far more than the sums and would otherwise be repeated by the 16 lanes of every row.
+  constexpr int NU = 8;
+  for (int n0 = tid >> 4; n0 < n_tiles * 16; n0 += 16 * NU) {
+    u32x4 v[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int n = n0 + 16 * u, ch = tid & 15;
+      v[u] = u32x4{0u, 0u, 0u, 0u};
+      if (n < l)
+        v[u] = *(const u32x4*)((n < st.n_tiled) ? Kh + (size_t)(n >> 4) * TILE_BYTES + ch * 256 + (n & 15) * 16
+                                                : Kh + (size_t)n * ROW_BYTES + ch * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int n = n0 + 16 * u;
+      double ss = 0.0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const double lo = (double)__uint_as_float(v[i] << 16), hi = (double)__uint_as_float(v[i] & 0xffff0000u);
+        const double lo = (double)__uint_as_float(v[u][i] << 16), hi = (double)__uint_as_float(v[u][i] & 0xffff0000u);
         ss = fma(lo, lo, ss);
         ss = fma(hi, hi, ss);
       }
+      ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4); ss += __shfl_xor(ss, 8);
+      if ((tid & 15) == 0 && n < n_tiles * 16) inv[n] = ss;
     }
-    ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4); ss += __shfl_xor(ss, 8);
-    if ((tid & 15) == 0) inv[n] = n < l ? 1.0 / (sqrt(ss) + (double)a.eps) : 0.0;
   }
   __syncthreads();
+  for (int n = tid; n < n_tiles * 16; n += 256) inv[n] = n < l ? 1.0 / (sqrt(inv[n]) + (double)a.eps) : 0.0;
+  __syncthreads();
 
-  // Each wavefront owns a contiguous share of the column tiles and takes NC of them per pass, so that
-  // each row tile fetched (from L2) is used NC times.
-  constexpr int NC = 5;
+  constexpr int NC = RED_NC;
   const int first_recent = l - a.n_recent;
   const double tau = (double)a.tau;
   const int per_wave = (n_tiles + 3) >> 2;
   const int J_end = min(n_tiles, (wave + 1) * per_wave);
-  for (int J0 = wave * per_wave; J0 < J_end; J0 += NC) {
+  const int n_pass = (per_wave + NC - 1) / NC;          // the same for all wavefronts: they share the barriers below
+  const int n_groups = (n_tiles + 3) >> 2;
+  // slot of (group parity, tile in group, 16-byte chunk c) for this lane: chunk-major, lane-minor
+  auto slot = [&](int par, int u, int c) { return ring + ((par * 4 + u) * 4 + c) * 1024 + lane * 16; };
+  auto ring_store = [&](int par, const u32x4 (&t)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) *(u32x4*)slot(par, wave, c) = t[c];
+  };
+  auto ring_load = [&](u32x4 (&t)[4], int par, int u) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) t[c] = *(const u32x4*)slot(par, u, c);
+  };
+
+  for (int p = 0; p < n_pass; ++p) {
+    const int J0 = wave * per_wave + p * NC;
     u32x4 colA[NC][4];
     double inv_j[NC];
     float thr[NC];
@@ -207,24 +243,27 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       if (T >= J0 && T < J0 + NC) row_tile(rowA, T, std::true_type{});
       else row_tile(rowA, T, std::false_type{});
     };
-    // Two row-tile buffers in turn: the next tile is requested before the current one is used (the
-    // tiles come from L2, and with four wavefronts per unit nothing else would cover that latency).
-    u32x4 rowA[4], rowB[4];
-    load_k_tile(rowA, Kh, 0, st.n_tiled, lane, r, kb);
-    // The column tiles are complete before the loop starts, so that the loop waits only for its own
-    // row tiles (the memory counter is in order: a wait for a column tile inside the loop would also
-    // wait for the row tile requested just before it).
+
+    u32x4 nxt[4];
+    load_k_tile(nxt, Kh, min(wave, n_tiles - 1), st.n_tiled, lane, r, kb);     // group 0
+    __syncthreads();                                      // the previous pass has finished with the ring
+    ring_store(0, nxt);
+    __syncthreads();
+    for (int G = 0; G < n_groups; ++G) {
+      const int par = G & 1;
+      // this wavefront's tile of the next group (clamped past the end: fetched, stored, never used)
+      load_k_tile(nxt, Kh, min(4 * (G + 1) + wave, n_tiles - 1), st.n_tiled, lane, r, kb);
+      u32x4 row[2][4];
+      ring_load(row[0], par, 0);
 #pragma unroll
-    for (int cc = 0; cc < NC; ++cc)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(colA[cc][c]));
-    // (requests past the last tile are clamped, not skipped: with the same number of requests in
-    // flight on every path, the wait for the current tile leaves the next one in flight)
-    for (int T = 0; T < n_tiles; T += 2) {
-      load_k_tile(rowB, Kh, min(T + 1, n_tiles - 1), st.n_tiled, lane, r, kb);
-      row_tile_any(rowA, T);
-      load_k_tile(rowA, Kh, min(T + 2, n_tiles - 1), st.n_tiled, lane, r, kb);
-      if (T + 1 < n_tiles) row_tile_any(rowB, T + 1);
+      for (int u = 0; u < 4; ++u) {
+        if (u < 3) ring_load(row[(u + 1) & 1], par, u + 1);
+        if (4 * G + u < n_tiles) row_tile_any(row[u & 1], 4 * G + u);
+      }
+      // the other half of the ring was last read in group G - 1, and every wavefront has passed
+      // the barrier that ended it
+      ring_store(par ^ 1, nxt);
+      __syncthreads();
     }
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
@@ -247,7 +286,15 @@ hipError_t gkv_launch_redundancy(const GkvLaunch& ln, const GkvDims& dm, int dty
   RedArgs a{K, d_state, step, F, lambda, tau, eps, n_recent, R_norm, F_sel};
   const int units = dm.L * dm.B * dm.Hkv;
   const size_t shmem = sizeof(double) * (2 * (size_t)dm.cap + 4);
-  if (mfma) return gkv_launch(ln, redundancy_mfma_kernel, dim3(units), dim3(256), shmem, dm, a);
+  if (mfma) {
+    const size_t with_ring = shmem + RED_RING_BYTES;
+    if (with_ring > 64 * 1024) {                         // beyond the default per-workgroup limit: opt in (a CU holds 160 KiB)
+      const hipError_t e = hipFuncSetAttribute((const void*)redundancy_mfma_kernel,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)with_ring);
+      if (e != hipSuccess) return e;
+    }
+    return gkv_launch(ln, redundancy_mfma_kernel, dim3(units), dim3(256), with_ring, dm, a);
+  }
   if (dtype == GKV_F32)
     return gkv_launch(ln, redundancy_generic_kernel<float>, dim3(units), dim3(256), shmem, dm, a);
   return gkv_launch(ln, redundancy_generic_kernel<uint16_t>, dim3(units), dim3(256), shmem, dm, a);

@@ -110,10 +110,15 @@ def check_redundancy_head(ev, j, R_gpu, Fsel_gpu, keep_gpu, red, w, k, what=""):
             base = col[jj] - vals[vals >= tau].sum()           # column sum without any of them
             if R_gpu[jj] <= 0:                                 # below fp32 range either way
                 continue
-            seen = colmax_gpu + logR[jj]
             cands = base + np.concatenate([[0.0], np.cumsum(vals)])     # entries all equal tau to 1e-6
-            m = int(np.argmin(np.abs(cands - seen)))
-            assert abs(cands[m] - seen) < 1e-3, f"{what}: column {jj} sum {seen} matches no reading {cands}"
+            # matched as R' values: the GPU's R' is an fp32 number and may be subnormal, where its
+            # logarithm no longer resolves 1e-3 (readings that give the same fp32 value cannot be
+            # told apart, and need not be: R' is what the path uses)
+            R_cands = np.exp(cands - colmax_gpu)
+            miss = np.abs(R_cands - float(R_gpu[jj]))
+            m = int(np.argmin(miss))
+            assert miss[m] <= 1e-3 * R_cands[m] + 3e-45, \
+                f"{what}: column {jj}: R' = {R_gpu[jj]} matches no reading {R_cands} (sums {cands})"
             col_gpu[jj] = cands[m]
             flipped += abs(m - int((vals >= tau).sum()))
     R_alt = O.softmax(col_gpu)

@@ -374,6 +374,29 @@ def test_redundancy_cfg5_shape_and_lambda_one():
     assert torch.equal(a["state"].V[..., :n, :], b["state"].V[..., :n, :])
 
 
+def test_redundancy_ragged_lengths_cfg3_shape():
+    # lengths 596, 633 and 640 at the first trigger: row and column tiles with ragged tails, column
+    # shares of unequal size per wavefront, clamped duplicates past the last tile
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=1, batch=3)
+    st = run_parity(wl, 640, prompts=[0, 37, 300], redundancy=dict(lam=0.7, tau=0.5, n_recent=wl.window),
+                    check_state_every_event=False)
+    lens = sorted({ev["len"] for orc in st["oracles"].values() for ev in orc.events})
+    _say(f"  lengths {lens}; entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) "
+         f"swaps {st['swaps']}")
+    assert {596, 633, 640} <= set(lens)
+    assert st["ambiguous"] <= 400 and st["flipped"] <= st["ambiguous"]
+
+
+def test_redundancy_b2048_shape():
+    # l = 2176: 136 tiles, seven passes per wavefront, and a workgroup needs more LDS than the default allowance
+    wl = CONFIGS["cfg4_b2048"].with_(n_layers=1, batch=1)
+    st = run_parity(wl, 2176, redundancy=dict(lam=0.7, tau=0.5, n_recent=wl.window), check_state_every_event=False,
+                    chunk=256)
+    assert st["events"] == 1
+    _say(f"  entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) swaps {st['swaps']}")
+    assert st["ambiguous"] <= 400 and st["flipped"] <= st["ambiguous"]
+
+
 def test_redundancy_closed_form_duplicate_keys():
     # orthogonal keys with one duplicated pair: R' = 1 for the pair, exp(-1) for everyone else
     st = _state("bf16", head_dim=128, n_q_heads=2, n_kv_heads=2, budget=32, window=4, interval=8, capacity=64)
