@@ -129,6 +129,25 @@ __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int 
 //
 // Dynamic LDS: double cs[cap]; double red[4]; double inv[cap]; then the ring, 2 groups x 4 tiles x 4 KiB
 constexpr int RED_NC = 5;
+
+// Sum over the 16 lanes of a DPP row (lanes 16i .. 16i+15), left in every one of them: lanes ^1
+// and ^2 of each quad, then the other quad of each 8 (mirror within 8: all four lanes of a quad
+// hold the same value by then), then the other 8 (mirror within 16).  Register-to-register, unlike
+// a shuffle through LDS, whose latency four dependent steps per row would pay in full.
+__device__ __forceinline__ double row16_sum(double v) {
+#define GKV_DPP_STEP(ctrl)                                                                         \
+  {                                                                                                \
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), ctrl, 0xF, 0xF, false);       \
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), ctrl, 0xF, 0xF, false);       \
+    v += __hiloint2double(hi, lo);                                                                 \
+  }
+  GKV_DPP_STEP(0xB1)    // quad_perm [1,0,3,2]
+  GKV_DPP_STEP(0x4E)    // quad_perm [2,3,0,1]
+  GKV_DPP_STEP(0x141)   // row_half_mirror
+  GKV_DPP_STEP(0x140)   // row_mirror
+#undef GKV_DPP_STEP
+  return v;
+}
 constexpr int RED_RING_BYTES = 2 * 4 * TILE_BYTES;
 
 __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArgs a) {
@@ -171,7 +190,7 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
         ss = fma(lo, lo, ss);
         ss = fma(hi, hi, ss);
       }
-      ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4); ss += __shfl_xor(ss, 8);
+      ss = row16_sum(ss);
       if ((tid & 15) == 0 && n < n_tiles * 16) inv[n] = ss;
     }
   }
