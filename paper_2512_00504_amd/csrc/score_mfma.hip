@@ -46,6 +46,18 @@ __device__ __forceinline__ float exp2_of(float z, float m, float hi, float lo) {
 
 // A operand of tile T: lane (row r, kblock kb) gets chunk 4c+kb of key 16T+r for c = 0..3; tiled
 // tiles are lane-contiguous, row-major tiles (rows appended since the last compaction) are not.
+// Sum over the 16 lanes of a DPP row (lanes 16i .. 16i+15), left in every one of them: lanes ^1
+// and ^2 of each quad, then the other quad of each 8 (mirror within 8: the four lanes of a quad
+// are equal by then), then the other 8 (mirror within 16).  Same pairs, same order as a butterfly
+// over lane ^1, ^2, ^4, ^8, so the same bits, without four dependent trips through LDS.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false));   // row_half_mirror
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, false));   // row_mirror
+  return v;
+}
+
 __device__ __forceinline__ void load_k_tile(u32x4 (&kA)[4], const char* Kh, int T, int n_tiled,
                                             int lane, int r, int kb) {
   const bool tiled = 16 * T < n_tiled;
@@ -193,9 +205,12 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
   float* So = a.S + (size_t)unit * cap;
   const int cand_tiles = (cc + 15) >> 4;
   const float wf = (float)W;
+  u32x4 kA[4], kN[4];
+  if (wave < cand_tiles) load_k_tile(kA, Kh, wave, seq.n_tiled, lane, r, kb);
   for (int T = wave; T < cand_tiles; T += NW) {
-    u32x4 kA[4];
-    load_k_tile(kA, Kh, T, seq.n_tiled, lane, r, kb);
+    // the wavefront's next tile is requested before this one is worked on (clamped at the end:
+    // the same number of requests in flight on every path keeps the wait for this tile short)
+    load_k_tile(kN, Kh, min(T + NW, cand_tiles - 1), seq.n_tiled, lane, r, kb);
     f32x4 tot = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < WT; ++nt) {
@@ -220,14 +235,12 @@ __global__ __launch_bounds__(NW * 64) void score_mfma_kernel(GkvDims dm, ScoreAr
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float v = tot[e];
-      v += __shfl_xor(v, 1);
-      v += __shfl_xor(v, 2);
-      v += __shfl_xor(v, 4);
-      v += __shfl_xor(v, 8);
+      const float v = row16_sum(tot[e]);
       const int key = 16 * T + 4 * kb + e;
       if (r == 0 && key < cc) { const float sv = v / wf; So[key] = sv; sbuf[key] = sv; }
     }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kA[c] = kN[c];
   }
 
   // ---- optional tail: global score of the candidates (Section 4), S still in LDS ---------------
