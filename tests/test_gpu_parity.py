@@ -397,6 +397,16 @@ def test_redundancy_b2048_shape():
     assert st["ambiguous"] <= 400 and st["flipped"] <= st["ambiguous"]
 
 
+def test_redundancy_largest_capacity():
+    # l = capacity = 3936: 246 tiles, 13 passes, 96 KiB of LDS per workgroup; sequence 1 (1096 rows) is left alone
+    wl = CONFIGS["cfg2_single_layer"].with_(n_layers=1, batch=2, budget=3840, interval=96, seed=41)
+    st = run_parity(wl, 96, prompts=[3840, 1000], redundancy=dict(lam=0.7, tau=0.5, n_recent=wl.window),
+                    chunk=96, check_state_every_event=False, say=_say)
+    assert st["pair_events"] == 1 and st["oracles"][(0, 0)].events[0]["len"] == 3936
+    _say(f"  entries on the threshold {st['ambiguous']} (decided the other way: {st['flipped']}) swaps {st['swaps']}")
+    assert st["ambiguous"] <= 400 and st["flipped"] <= st["ambiguous"]
+
+
 def test_redundancy_closed_form_duplicate_keys():
     # orthogonal keys with one duplicated pair: R' = 1 for the pair, exp(-1) for everyone else
     st = _state("bf16", head_dim=128, n_q_heads=2, n_kv_heads=2, budget=32, window=4, interval=8, capacity=64)
