@@ -166,6 +166,21 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   const char* Kh = (const char*)a.K + (size_t)unit * dm.cap * ROW_BYTES;
   const int n_tiles = (l + 15) >> 4;
 
+  constexpr int NC = RED_NC;
+  const int per_wave = (n_tiles + 3) >> 2;
+  // The column tiles of a pass and this wavefront's tile of the first ring group, requested as
+  // early as their registers are free: for pass 0 before the norms (which they do not depend
+  // on), for the later passes when the previous pass has used its last row tile.
+  u32x4 colA[NC][4], nxt[4];
+  auto request_pass = [&](int p) {
+    const int J0 = wave * per_wave + p * NC;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc)                         // past the last tile: a clamped duplicate, computed and dropped
+      load_k_tile(colA[cc], Kh, min(J0 + cc, n_tiles - 1), st.n_tiled, lane, r, kb);
+    load_k_tile(nxt, Kh, min(wave, n_tiles - 1), st.n_tiled, lane, r, kb);
+  };
+  request_pass(0);
+
   // Row norms.  Squared norms first, a quarter-wave per row and 16 bytes per lane, eight rows' loads
   // issued together; then one row per thread for the fp64 square root and reciprocal, which cost
   // far more than the sums and would otherwise be repeated by the 16 lanes of every row.
@@ -198,10 +213,8 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
   for (int n = tid; n < n_tiles * 16; n += 256) inv[n] = n < l ? 1.0 / (sqrt(inv[n]) + (double)a.eps) : 0.0;
   __syncthreads();
 
-  constexpr int NC = RED_NC;
   const int first_recent = l - a.n_recent;
   const double tau = (double)a.tau;
-  const int per_wave = (n_tiles + 3) >> 2;
   const int J_end = min(n_tiles, (wave + 1) * per_wave);
   const int n_pass = (per_wave + NC - 1) / NC;          // the same for all wavefronts: they share the barriers below
   const int n_groups = (n_tiles + 3) >> 2;
@@ -218,14 +231,12 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
 
   for (int p = 0; p < n_pass; ++p) {
     const int J0 = wave * per_wave + p * NC;
-    u32x4 colA[NC][4];
     double inv_j[NC];
     float thr[NC];
     double col[NC];
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
-      const int J = min(J0 + cc, n_tiles - 1);            // a clamped duplicate is computed and dropped
-      load_k_tile(colA[cc], Kh, J, st.n_tiled, lane, r, kb);
+      const int J = min(J0 + cc, n_tiles - 1);
       inv_j[cc] = inv[16 * J + r];
       // C = dot * inv_k * inv_j >= tau  <=>  dot * inv_k >= tau / inv_j: one product per entry, the
       // column's factor applied once to the sum (columns >= l have inv_j = 0 and are dropped below)
@@ -263,10 +274,7 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       else row_tile(rowA, T, std::false_type{});
     };
 
-    u32x4 nxt[4];
-    load_k_tile(nxt, Kh, min(wave, n_tiles - 1), st.n_tiled, lane, r, kb);     // group 0
-    __syncthreads();                                      // the previous pass has finished with the ring
-    ring_store(0, nxt);
+    ring_store(0, nxt);                                   // group 0 (the previous pass ended with a barrier after its last reads)
     __syncthreads();
     for (int G = 0; G < n_groups; ++G) {
       const int par = G & 1;
@@ -284,6 +292,7 @@ __global__ __launch_bounds__(256) void redundancy_mfma_kernel(GkvDims dm, RedArg
       ring_store(par ^ 1, nxt);
       __syncthreads();
     }
+    if (p + 1 < n_pass) request_pass(p + 1);              // travels while the column sums are put together
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) {
       double v = col[cc];
