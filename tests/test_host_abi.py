@@ -140,3 +140,13 @@ def test_k_offset_matches_the_layout_permutation():
     assert P.k_offset(_cfg(dtype="bf16"), 17, 9, 32) == 1024 + 128 + 8 + 1
     assert P.k_offset(_cfg(dtype="bf16"), 17, 9, 16) == 17 * 64 + 9
     assert P.k_offset(_cfg(), -1, 0, 0) == -1 and P.k_offset(_cfg(), 0, 64, 0) == -1
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    # one GPU is all this build measures: asking for more ends with a message, before any GPU work
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "--gpus must be 1" in (res.stdout + res.stderr)
