@@ -65,9 +65,15 @@ __global__ __launch_bounds__(256) void global_update_kernel(GkvDims dm, const fl
 }
 
 // ---- top-(b-w): exact radix select on the float bits, ties to the lower index ---------------
+// WITH_UPDATE: F points at the local score S instead, and the kernel first forms the global score
+// from it and F_hist exactly as global_update_kernel does (same expressions, same bits), writes
+// it to F_out and selects on it: one launch less per compression.
 // Dynamic LDS: uint32 keys[cap]
+template <bool WITH_UPDATE>
 __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const float* __restrict__ F,
+                                                          const float* __restrict__ F_hist,
                                                           const int32_t* __restrict__ d_state, int step,
+                                                          float* __restrict__ F_out,
                                                           int32_t* __restrict__ keep_idx) {
   step = resolve_step(dm, step);
   extern __shared__ uint32_t keys[];
@@ -75,12 +81,36 @@ __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const floa
   __shared__ int tmp[4];
   __shared__ int sel[2];
   const int unit = blockIdx.x, lb = unit / dm.Hkv, tid = threadIdx.x;
-  const int l = compression_length(load_state(d_state, lb), step, dm.b, dm.w, dm.cap);
+  const SeqState st = load_state(d_state, lb);
+  const int l = compression_length(st, step, dm.b, dm.w, dm.cap);
   if (l == 0) return;
   const int c = l - dm.w;
   const int k = dm.b - dm.w;                   // c > k because l > b
   const float* Fu = F + (size_t)unit * dm.cap;
-  for (int n = tid; n < c; n += 256) keys[n] = sortable_key(Fu[n]);
+  if constexpr (WITH_UPDATE) {
+    __shared__ float red[8];
+    int n_hist = st.n_hist;
+    n_hist = n_hist < 0 ? 0 : (n_hist > c ? c : n_hist);
+    const float* Hu = F_hist + (size_t)unit * dm.cap;
+    float* Fo = F_out + (size_t)unit * dm.cap;
+    float mx = 0.f;
+    for (int n = tid; n < c; n += 256) mx = fmaxf(mx, Fu[n]);
+    mx = block_max(mx, red);
+    for (int n = tid; n < c; n += 256) {
+      const float sn = mx > 0.f ? Fu[n] / mx : 0.f;
+      float f = sn;
+      if (n < n_hist) {
+        const float h = dm.alpha * Hu[n];
+        f = dm.combine == GKV_COMBINE_MAX ? fmaxf(h, sn)
+          : dm.combine == GKV_COMBINE_AVG ? h + (1.f - dm.alpha) * sn
+                                          : h + sn;
+      }
+      Fo[n] = f;
+      keys[n] = sortable_key(f);
+    }
+  } else {
+    for (int n = tid; n < c; n += 256) keys[n] = sortable_key(Fu[n]);
+  }
 
   uint32_t prefix = 0, mask = 0;
   int krem = k;
@@ -311,8 +341,15 @@ hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, cons
 hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
                                   const int32_t* d_state, int32_t step, int32_t* keep_idx) {
   const int units = dm.L * dm.B * dm.Hkv;
-  return gkv_launch(ln, select_topk_kernel, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, F, d_state,
-                    (int)step, keep_idx);
+  return gkv_launch(ln, select_topk_kernel<false>, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, F,
+                    (const float*)nullptr, d_state, (int)step, (float*)nullptr, keep_idx);
+}
+
+hipError_t gkv_launch_update_and_select(const GkvLaunch& ln, const GkvDims& dm, const float* S, const float* F_hist,
+                                        const int32_t* d_state, int32_t step, float* F_out, int32_t* keep_idx) {
+  const int units = dm.L * dm.B * dm.Hkv;
+  return gkv_launch(ln, select_topk_kernel<true>, dim3(units), dim3(256), sizeof(uint32_t) * dm.cap, dm, S, F_hist,
+                    d_state, (int)step, F_out, keep_idx);
 }
 
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,

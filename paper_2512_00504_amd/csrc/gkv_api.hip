@@ -112,6 +112,7 @@ extern "C" gkv_status gkv_create(const gkv_config* cfg, gkv_ctx** out_ctx) {
   c->reuse_stats = 1;
   c->compact_ppt = 8;
   c->fuse_global = 0;
+  c->fuse_select = 1;
   c->attend_waves = 0;
   c->stats_step = new (std::nothrow) int32_t[cfg->window];
   if (!c->stats_step) { delete c; return GKV_ERR_INVALID_ARG; }
@@ -261,6 +262,7 @@ extern "C" gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t valu
     return GKV_OK;
   }
   if (!strcmp(name, "evict_fuse_global")) { ctx->fuse_global = value != 0; return GKV_OK; }
+  if (!strcmp(name, "evict_fuse_select")) { ctx->fuse_select = value != 0; return GKV_OK; }
   if (!strcmp(name, "score_reuse_stats")) { ctx->reuse_stats = value != 0; return GKV_OK; }
   return GKV_ERR_INVALID_ARG;
 }
@@ -407,6 +409,14 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
   } else {
     st = gkv_score_window(ctx, qwin, K, d_state, step, len_max_host, S, workspace, stream);
     if (st != GKV_OK) return st;
+    if (ctx->fuse_select) {
+      // the global score is formed at the head of the selection kernel (same arithmetic as
+      // gkv_global_update, F written as well): four launches per compression instead of five
+      GkvLaunch ln{ctx, GKV_K_TOPK, (hipStream_t)stream};
+      st = hip_status(gkv_launch_update_and_select(ln, ctx->dims, S, F_hist, d_state, step, F, keep_idx));
+      if (st != GKV_OK) return st;
+      return gkv_compact(ctx, keep_idx, F, K, V, F_hist, pos, d_state, step, workspace, stream);
+    }
     st = gkv_global_update(ctx, S, F_hist, d_state, step, len_max_host, F, stream);
     if (st != GKV_OK) return st;
   }

@@ -35,6 +35,7 @@ struct gkv_ctx {
   int32_t force_generic;
   int32_t attend_waves;   // 0 = automatic
   int32_t fuse_global;    // gkv_evict: global score in the tail of the window-score kernel
+  int32_t fuse_select;    // gkv_evict: global score at the head of the top-k kernel (default)
   int32_t compact_ppt;    // 16-byte pieces per thread and chunk round of the compaction kernel: 4, 8 or 16
   int32_t reuse_stats;    // window score may reuse the softmax statistics the decode kernel recorded
   bool mfma_ok;           // bf16, d == 128, g <= 16
@@ -97,6 +98,8 @@ hipError_t gkv_launch_global_update(const GkvLaunch& ln, const GkvDims& dm, cons
                                     const float* F_hist, const int32_t* d_state, int32_t step, float* F_out);
 hipError_t gkv_launch_select_topk(const GkvLaunch& ln, const GkvDims& dm, const float* F,
                                   const int32_t* d_state, int32_t step, int32_t* keep_idx);
+hipError_t gkv_launch_update_and_select(const GkvLaunch& ln, const GkvDims& dm, const float* S, const float* F_hist,
+                                        const int32_t* d_state, int32_t step, float* F_out, int32_t* keep_idx);
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
                               int32_t* d_state, int32_t step);

@@ -95,6 +95,16 @@ def test_cfg3_shape_evict_with_the_global_score_in_the_score_kernels_tail():
     assert st["events"] == 3
 
 
+def test_evict_with_the_global_score_in_a_launch_of_its_own():
+    # gkv_evict forms the global score at the head of the selection kernel by default; with that
+    # switched off it takes the gkv_global_update launch: same results (both against the oracle)
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2, combine="avg")
+    st = run_parity(wl, 1024, fused_evict=True, params={"evict_fuse_select": 0}, check_state_every_event=False)
+    assert st["events"] == 4
+    st = run_parity(CONFIGS["cfg1_tiny"], 128, fused_evict=True, params={"evict_fuse_select": 0})
+    assert st["events"] == 4
+
+
 def test_cfg3_shape_32_key_slices():
     # the other slice size of the matrix-core attend kernel
     wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=2)
