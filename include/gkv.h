@@ -224,6 +224,8 @@ gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_t* d_state,
  * F_hist[r] = F[keep_idx[r]], the w window rows [l-w, l) move to [b-w, b).  K rows
  * below b rounded down to 16 are written in tiled format.  Then d_state becomes
  * {b, step + 1, b - w, b rounded down to 16}.  F must not alias F_hist.
+ * workspace may be NULL: the state records are then rewritten by a second small launch
+ * instead of by the last workgroup of each (layer, sequence).
  */
 gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
                        float* F_hist, int32_t* pos, int32_t* d_state, int32_t step,

@@ -167,12 +167,17 @@ __global__ __launch_bounds__(256) void select_topk_kernel(GkvDims dm, const floa
 // source piece of a chunk is loaded, then a barrier, then the stores.  Destination index <=
 // source index and sources ascend, so a chunk's stores (which stay inside the chunk's tiles)
 // never touch a row that a later chunk still has to read.
+// State record: every workgroup reads it at its start.  With a ticket array (one counter per
+// (layer, sequence), zero between launches) the workgroup that finishes last among the 2 h_kv of
+// a (layer, sequence) knows that all of them have read the record, and rewrites it; no data
+// depends on that write inside this launch, so the counter needs no fence.  Without a ticket
+// array a separate launch rewrites the records.
 // Dynamic LDS: int keep_s[b - w]: the kept indices, read from memory once.
 template <int PPT>
 __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const int32_t* __restrict__ keep_idx,
                                                       const float* __restrict__ F, void* K, void* V,
                                                       float* __restrict__ F_hist, int32_t* pos,
-                                                      const int32_t* __restrict__ d_state, int step) {
+                                                      int32_t* d_state, int step, int32_t* state_ticket) {
   step = resolve_step(dm, step);
   extern __shared__ int keep_s[];
   __shared__ int red_i[4];
@@ -247,6 +252,14 @@ __global__ __launch_bounds__(256) void compact_kernel(GkvDims dm, int esz, const
     for (int i = 0; i < PPT; ++i)
       if (dst[i] >= 0) base[dst[i]] = buf[i];
     if (do_pos) pu[prow] = pos_val;
+  }
+  // (every wavefront of this workgroup passed the barrier above after reading the record)
+  if (state_ticket != nullptr && tid == 0) {
+    const int done = atomicAdd(&state_ticket[lb], 1);
+    if (done == 2 * dm.Hkv - 1) {
+      state_ticket[lb] = 0;
+      *(int4*)(d_state + 4 * (size_t)lb) = make_int4(dm.b, step + 1, dm.b - dm.w, dm.b & ~15);
+    }
   }
 }
 
@@ -354,14 +367,14 @@ hipError_t gkv_launch_update_and_select(const GkvLaunch& ln, const GkvDims& dm, 
 
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
-                              int32_t* d_state, int32_t step) {
+                              int32_t* d_state, int32_t step, int32_t* state_ticket) {
   const int units = dm.L * dm.B * dm.Hkv;
   const size_t shmem = sizeof(int) * (size_t)(dm.b - dm.w);
   const int ppt = ln.ctx ? ln.ctx->compact_ppt : 8;
   auto kern = ppt == 16 ? compact_kernel<16> : ppt == 8 ? compact_kernel<8> : compact_kernel<4>;
   hipError_t e = gkv_launch(ln, kern, dim3(units, 2), dim3(256), shmem, dm, esz, keep_idx, F, K, V,
-                            F_hist, pos, (const int32_t*)d_state, (int)step);
-  if (e != hipSuccess) return e;
+                            F_hist, pos, d_state, (int)step, state_ticket);
+  if (e != hipSuccess || state_ticket != nullptr) return e;
   const int nlb = dm.L * dm.B;
   GkvLaunch plain{ln.ctx, -1, ln.stream};
   return gkv_launch(plain, finalize_state_kernel, dim3((nlb + 255) / 256), dim3(256), 0, dm, d_state, (int)step);

@@ -192,6 +192,7 @@ GkvWorkspace gkv_carve_workspace(const gkv_ctx* ctx, void* base) {
   char* p = (char*)base;
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
   w.split_ticket = (int32_t*)p; p += gkv_align256(units * 4);
+  w.state_ticket = (int32_t*)p; p += gkv_align256((size_t)ctx->dims.L * ctx->dims.B * 4);
   w.stats = (float2*)p; p += gkv_align256(ws_stats_bytes(ctx));
   w.partials = (float*)p;
   return w;
@@ -202,7 +203,8 @@ extern "C" gkv_status gkv_workspace_bytes(gkv_ctx* ctx, size_t* out_bytes) {
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
   // the workspace is sized for the split count in force now; the decode call refuses a larger one
   ctx->ws_splits = gkv_effective_splits(ctx);
-  *out_bytes = gkv_align256(units * 4) + gkv_align256(ws_stats_bytes(ctx)) +
+  *out_bytes = gkv_align256(units * 4) + gkv_align256((size_t)ctx->dims.L * ctx->dims.B * 4) +
+               gkv_align256(ws_stats_bytes(ctx)) +
                gkv_align256(ws_partials_bytes(ctx, ctx->ws_splits)) + 256;
   return GKV_OK;
 }
@@ -211,7 +213,7 @@ extern "C" gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* st
   if (!ctx) return GKV_ERR_INVALID_ARG;
   if (!workspace) return GKV_ERR_WORKSPACE;
   const size_t units = (size_t)ctx->dims.L * ctx->dims.B * ctx->dims.Hkv;
-  const size_t n = gkv_align256(units * 4) / 4;
+  const size_t n = (gkv_align256(units * 4) + gkv_align256((size_t)ctx->dims.L * ctx->dims.B * 4)) / 4;   // both ticket arrays
   return gkv_launch_fill_zero((hipStream_t)stream, (int32_t*)workspace, n) == hipSuccess ? GKV_OK : GKV_ERR_HIP;
 }
 
@@ -384,11 +386,13 @@ extern "C" gkv_status gkv_select_topk(gkv_ctx* ctx, const float* F, const int32_
 extern "C" gkv_status gkv_compact(gkv_ctx* ctx, const int32_t* keep_idx, const float* F, void* K, void* V,
                                   float* F_hist, int32_t* pos, int32_t* d_state, int32_t step,
                                   void* workspace, void* stream) {
-  (void)workspace;
   if (!ctx || !keep_idx || !F || !K || !V || !F_hist || !pos || !d_state || step < 0) return GKV_ERR_INVALID_ARG;
   if (F == F_hist) return GKV_ERR_INVALID_ARG;
   GkvLaunch ln{ctx, GKV_K_COMPACT, (hipStream_t)stream};
-  return hip_status(gkv_launch_compact(ln, ctx->dims, ctx->esz, keep_idx, F, K, V, F_hist, pos, d_state, step));
+  // with a workspace the last compaction workgroup of a (layer, sequence) rewrites its state
+  // record; without one a second small launch does
+  int32_t* ticket = workspace ? gkv_carve_workspace(ctx, workspace).state_ticket : nullptr;
+  return hip_status(gkv_launch_compact(ln, ctx->dims, ctx->esz, keep_idx, F, K, V, F_hist, pos, d_state, step, ticket));
 }
 
 extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V, float* F_hist, int32_t* pos,

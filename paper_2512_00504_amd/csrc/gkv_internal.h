@@ -55,6 +55,7 @@ struct gkv_ctx {
 //   [.., + 4*units*splits*g*(d+2))  split-K partials (float)
 struct GkvWorkspace {
   int32_t* split_ticket;
+  int32_t* state_ticket;  // [L*B]: compaction workgroups of a (layer, sequence) that have finished; zero between launches
   float2* stats;
   float* partials;
 };
@@ -102,7 +103,7 @@ hipError_t gkv_launch_update_and_select(const GkvLaunch& ln, const GkvDims& dm, 
                                         const int32_t* d_state, int32_t step, float* F_out, int32_t* keep_idx);
 hipError_t gkv_launch_compact(const GkvLaunch& ln, const GkvDims& dm, int esz, const int32_t* keep_idx,
                               const float* F, void* K, void* V, float* F_hist, int32_t* pos,
-                              int32_t* d_state, int32_t step);
+                              int32_t* d_state, int32_t step, int32_t* state_ticket);
 hipError_t gkv_launch_redundancy(const GkvLaunch& ln, const GkvDims& dm, int dtype, bool mfma, const void* K,
                                  const int32_t* d_state, int32_t step, const float* F, float lambda, float tau,
                                  float eps, int32_t n_recent, float* R_norm, float* F_sel);

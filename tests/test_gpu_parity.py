@@ -95,6 +95,40 @@ def test_cfg3_shape_evict_with_the_global_score_in_the_score_kernels_tail():
     assert st["events"] == 3
 
 
+def test_compaction_without_a_workspace_rewrites_the_state_in_a_second_launch():
+    # same compaction twice from the same state: with the workspace (the last workgroup of each
+    # (layer, sequence) rewrites the record) and without (a launch of its own does): same bits
+    wl = CONFIGS["cfg3_28layer_b512"].with_(n_layers=2, batch=3)
+    from gkv_traces import Trace
+    tr = Trace(wl)
+    n = wl.budget + wl.interval
+    q, k, v = [torch.from_numpy(x).to(torch.bfloat16).cuda() for x in tr.batch_steps(0, n)]
+    results = []
+    for use_ws in (True, False):
+        st = DecodeState.from_workload(wl)
+        for t in range(n):
+            st.attend_decode(q[t], k[t], v[t], t)
+        st.score_window(n - 1); st.global_update(n - 1); st.select_topk(n - 1)
+        st.ctx.compact(st.keep_idx, st.F, st.K, st.V, st.F_hist, st.pos, st.d_state, n - 1,
+                       st.workspace if use_ws else None)
+        torch.cuda.synchronize()
+        assert (st.d_state[..., 0] == wl.budget).all() and (st.d_state[..., 1] == n).all()
+        results.append([x.clone() for x in (st.K, st.V, st.pos, st.F_hist, st.d_state)])
+    for a_, b_ in zip(*results):
+        assert torch.equal(a_.view(torch.uint8), b_.view(torch.uint8))
+    # and the ticket counters are back at zero: a second compression on the same workspace works
+    st = DecodeState.from_workload(wl)
+    q2, k2, v2 = [torch.from_numpy(x).to(torch.bfloat16).cuda() for x in tr.batch_steps(n, wl.interval)]
+    for t in range(n):
+        st.attend_decode(q[t], k[t], v[t], t)
+    st.evict(n - 1)
+    for i in range(wl.interval):
+        st.attend_decode(q2[i], k2[i], v2[i], n + i)
+    st.evict(n + wl.interval - 1)
+    torch.cuda.synchronize()
+    assert (st.d_state[..., 0] == wl.budget).all() and (st.d_state[..., 1] == n + wl.interval).all()
+
+
 def test_evict_with_the_global_score_in_a_launch_of_its_own():
     # gkv_evict forms the global score at the head of the selection kernel by default; with that
     # switched off it takes the gkv_global_update launch: same results (both against the oracle)
