@@ -137,8 +137,8 @@ int64_t gkv_k_offset(const gkv_config* cfg, int32_t row, int32_t channel, int32_
  * gkv_score_window), "evict_fuse_global" (1 = gkv_evict computes the global score in the tail
  * of the matrix-core window-score kernel, S still in LDS, instead of a launch of its own;
  * same results, measured neither faster nor slower), "evict_fuse_select" (default 1: gkv_evict
- * forms the global score at the head of the selection kernel, four launches per compression
- * instead of five; 0 = a launch of its own as in gkv_global_update; same bits either way). */
+ * forms the global score at the head of the selection kernel, one launch less per compression;
+ * 0 = a launch of its own as in gkv_global_update; same bits either way). */
 gkv_status gkv_set_param(gkv_ctx* ctx, const char* name, int32_t value);
 
 /*

@@ -415,7 +415,7 @@ extern "C" gkv_status gkv_evict(gkv_ctx* ctx, const void* qwin, void* K, void* V
     if (st != GKV_OK) return st;
     if (ctx->fuse_select) {
       // the global score is formed at the head of the selection kernel (same arithmetic as
-      // gkv_global_update, F written as well): four launches per compression instead of five
+      // gkv_global_update, F written as well): one launch less per compression
       GkvLaunch ln{ctx, GKV_K_TOPK, (hipStream_t)stream};
       st = hip_status(gkv_launch_update_and_select(ln, ctx->dims, S, F_hist, d_state, step, F, keep_idx));
       if (st != GKV_OK) return st;
