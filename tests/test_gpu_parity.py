@@ -127,6 +127,10 @@ def test_compaction_without_a_workspace_rewrites_the_state_in_a_second_launch():
     st.evict(n + wl.interval - 1)
     torch.cuda.synchronize()
     assert (st.d_state[..., 0] == wl.budget).all() and (st.d_state[..., 1] == n + wl.interval).all()
+    units = wl.n_layers * wl.batch * wl.n_kv_heads
+    off = ((units * 4 + 255) & ~255) // 4                  # the per-(layer, sequence) counters follow the per-unit ones
+    tickets = st.workspace[: 4 * (off + wl.n_layers * wl.batch)].view(torch.int32)
+    assert int(tickets.abs().sum()) == 0
 
 
 def test_evict_with_the_global_score_in_a_launch_of_its_own():
