@@ -112,8 +112,10 @@ const char* gkv_status_string(gkv_status st);
  * are now; the context remembers the "attend_splits" value the size covers, and
  * gkv_attend_decode returns GKV_ERR_WORKSPACE if the knob was raised afterwards. */
 gkv_status gkv_workspace_bytes(gkv_ctx* ctx, size_t* out_bytes);
-/* Enqueues a fill kernel that zeroes the workspace's counters (used only when one
- * unit's attention is split over several workgroups).  Call once. */
+/* Enqueues a fill kernel that zeroes the workspace's counters (one per unit, used when a
+ * unit's attention is split over several workgroups; one per (layer, sequence), used by the
+ * compaction to find the workgroup that finishes last).  The kernels leave them at zero.
+ * Call once, before the first call that takes the workspace. */
 gkv_status gkv_workspace_init(gkv_ctx* ctx, void* workspace, void* stream);
 
 /* Host-only helpers.
